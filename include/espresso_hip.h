@@ -1,0 +1,177 @@
+/*
+ * espresso_hip.h -- C ABI of the MI355X (gfx950) binary-network forward library.
+ *
+ * The library implements the bit-packed forward path of Espresso
+ * (arXiv 1705.07175): binary dense and convolutional layers whose dot products
+ * are evaluated on 64-bit packed words (Sec. 4.2, Eq. 2), plus the supporting
+ * steps around them (bit-packing, unrolling, batch-norm + sign re-packing,
+ * pooling, and the real-valued first layer).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  * Encoding (Sec. 4.1): -1 is bit 0, +1 is bit 1.  sign(x) = +1 iff x >= 0
+ *    (Eq. 1), so 0.0 and -0.0 give bit 1 and NaN gives bit 0.
+ *  * Packing (Sec. 4.2, Sec. 5.1): values are packed along their last
+ *    dimension (K for matrices, the channel l for NHWC tensors) into uint64
+ *    words.  Element k lives in word k/64, bit k%64, least significant bit
+ *    first.  A row of K values takes Kw = ceil(K/64) words; the unused high
+ *    bits of its last word are 0 in every buffer the library writes and MUST
+ *    be 0 in every packed buffer it reads.
+ *  * Tensors (Sec. 5.1): row-major with interleaved channels, element (m,n,l)
+ *    at (m*N+n)*L+l, with the batch index prepended: [B][H][W][C] ("NHWC").
+ *    Dense weights and convolution filters hold one neuron/filter per row.
+ *  * Memory: unless a parameter is marked HOST, every pointer is DEVICE memory
+ *    owned by the caller (the paper pre-allocates all memory, Sec. 3
+ *    "Technical highlights"; here the caller does).  The library never
+ *    allocates, frees or synchronises.  Outputs are overwritten completely,
+ *    inputs are never modified, inputs and outputs must not overlap.
+ *  * Execution: every device entry point only enqueues kernels on `stream`
+ *    (a hipStream_t passed as void*; NULL is the default stream) and returns.
+ *  * Errors: the return value is ESP_OK or a negative esp_status.  Nothing is
+ *    enqueued when an error is returned.  The library never throws, aborts or
+ *    prints.  uint64 buffers must be 8-byte aligned, int32/float buffers
+ *    4-byte aligned (ESP_EALIGN otherwise); 16-byte alignment of every base
+ *    pointer enables the fastest paths.
+ *  * Sizes: 0 < K < 2^30 so that |dot| fits int32; a dimension of 0 rows
+ *    (rows, M, B) is accepted and does nothing; other non-positive
+ *    dimensions give ESP_EINVAL.
+ */
+#ifndef ESPRESSO_HIP_H
+#define ESPRESSO_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *esp_stream; /* hipStream_t; NULL = default stream */
+
+enum esp_status {
+    ESP_OK = 0,
+    ESP_EINVAL = -1,     /* null pointer, negative or zero dimension              */
+    ESP_EALIGN = -2,     /* a buffer is not aligned for its element type          */
+    ESP_ESHAPE = -3,     /* shapes inconsistent (kernel larger than padded input, */
+                         /* stride < 1, pad < 0, pooled size 0, K >= 2^30, ...)   */
+    ESP_EWORKSPACE = -4, /* workspace missing or too small                        */
+    ESP_ELAUNCH = -5     /* the HIP runtime refused a launch                      */
+};
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *esp_strerror(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int esp_version(void);
+
+/* ------------------------------------------------------------------------- */
+/* pack: sign (Eq. 1) + bit-packing along the row (Sec. 4.2; the row-packing  */
+/* kernel of Sec. 6.2 "Optimized kernels").                                   */
+/*   src  float [rows][k]           dst  uint64 [rows][ceil(k/64)]            */
+/* Weights are packed once at load time, not per forward (Sec. 6.2 "Binary    */
+/* optimized layers").  An NHWC tensor is packed along channels by passing    */
+/* rows = B*H*W, k = C.                                                        */
+/* ------------------------------------------------------------------------- */
+int esp_pack_f32(const float *src, uint64_t *dst, int64_t rows, int64_t k, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* bgemm: binary matrix product (Sec. 4.2, Eq. 2; kernel design prior art in  */
+/* Sec. 5.2 "Efficient Matrix multiplication", sizes of Sec. 6.1).            */
+/*   A  uint64 [M][Kw]   packed activations, one input row per row            */
+/*   B  uint64 [N][Kw]   packed weights, one neuron per row                   */
+/*   C  int32  [M][N]    C[m][n] = K - 2 * sum_w popcount(A[m][w] XOR B[n][w])*/
+/* which equals the dot product of the two +-1 rows of true length K          */
+/* (Kw = ceil(K/64); zero tail bits cancel in the XOR).  Eq. 2 as printed     */
+/* counts matches and subtracts them, which would negate the result; the      */
+/* mismatch form above is the one that equals the +-1 dot product.            */
+/* Any M >= 0, N > 0; small M (matrix-vector, Sec. 6.2 "Optimized kernels")   */
+/* is dispatched to a bandwidth-oriented kernel.                              */
+/* ------------------------------------------------------------------------- */
+int esp_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C,
+              int64_t M, int64_t N, int64_t K, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* unroll: packed im2col (Sec. 5.2 "Convolutional layers", Fig. 3).           */
+/*   in   uint64 [B][H][W][Cw]                  Cw = ceil(C/64)               */
+/*   out  uint64 [B*H2*W2][kh*kw*Cw]            H2 = (H+2*pad-kh)/stride+1    */
+/* Row (b*H2+m)*W2+n holds the sliding volume in[b][m*s-p .. +kh][n*s-p ..    */
+/* +kw][:] tap by tap: word (dy*kw+dx)*Cw + w.  Taps outside the image are    */
+/* all-zero words, i.e. the value -1 (Sec. 5.2 "Zero-padding for              */
+/* convolutions": the border is treated as -1).                               */
+/* ------------------------------------------------------------------------- */
+int esp_unroll(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
+               int kh, int kw, int stride, int pad, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* bconv: binary convolution = unroll + bgemm (Sec. 5.2, Fig. 3); the output  */
+/* rows are already NHWC so no lifting step exists.                           */
+/*   in    uint64 [B][H][W][Cw]                                               */
+/*   filt  uint64 [L2][kh][kw][Cw]   one filter per row, taps in unroll order */
+/*   out   int32  [B][H2][W2][L2]    +-1 cross-correlation over kh*kw*C taps, */
+/*                                    border = -1                             */
+/*   workspace  device scratch of at least esp_bconv_workspace_bytes(...)     */
+/*              bytes, 16-byte aligned (holds the lowered matrix).            */
+/* ------------------------------------------------------------------------- */
+size_t esp_bconv_workspace_bytes(int B, int H, int W, int C, int kh, int kw, int stride, int pad);
+
+int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
+              int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+              void *workspace, size_t workspace_bytes, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* bn_fold (HOST function, run once per layer at load time): folds inference  */
+/* batch-norm followed by sign (Sec. 5.2 lists the batch-norm layer; Eq. 1)   */
+/* into one integer threshold per channel.  With                              */
+/*   y(x) = gamma*(x-mean)/sqrt(var+eps) + beta   evaluated in double, left   */
+/*   to right, no fused multiply-add,                                         */
+/* the outputs satisfy, for every integer |x| <= 2^30,                        */
+/*   (y(x) >= 0)  ==  (x >= thr[c]) XOR flipbit(c)                            */
+/* where flipbit(c) is bit c%64 of flip[c/64].                                */
+/*   gamma, beta, mean, var   HOST float [C]                                  */
+/*   thr   HOST int32 [C]       flip  HOST uint64 [ceil(C/64)]                */
+/* ------------------------------------------------------------------------- */
+int esp_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
+                float eps, int C, int32_t *thr, uint64_t *flip);
+
+/* ------------------------------------------------------------------------- */
+/* bn_sign_pack: batch-norm + sign + re-pack of an integer layer output (the  */
+/* bit-packing sign activation of Sec. 6.3 "Bit-packing"), using the folded   */
+/* threshold:  bit c of row r = (x[r][c] >= thr[c]) XOR flipbit(c).           */
+/*   x  int32 [rows][C]   thr int32 [C]   flip uint64 [Cw]   out uint64 [rows][Cw] */
+/* ------------------------------------------------------------------------- */
+int esp_bn_sign_pack(const int32_t *x, const int32_t *thr, const uint64_t *flip,
+                     uint64_t *out, int64_t rows, int C, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* bmaxpool: max-pooling of +-1 activations on packed words (pooling layer of */
+/* Sec. 5.2): the maximum of +-1 values is the bitwise OR of their bits.      */
+/*   in  uint64 [B][H][W][Cw]   out uint64 [B][H2][W2][Cw]                    */
+/*   H2 = (H-win)/stride + 1 (floor), no padding.                             */
+/* ------------------------------------------------------------------------- */
+int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
+                 int win, int stride, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* Real-valued first layer (the non-binary variant of a layer, Sec. 3; the    */
+/* networks of Sec. 6.2 / 6.3 receive real-valued images).  fp32 arithmetic.  */
+/*   dense:  X float [M][K], W float [N][K] (+-1 values), Y float [M][N]      */
+/*   conv :  in float [B][H][W][C], filt float [L2][kh][kw][C] (+-1 values),  */
+/*           out float [B][H2][W2][L2], zero padding                          */
+/*   bn_sign_pack_f32: y as in esp_bn_fold evaluated in double on the GPU,    */
+/*           bit = (y >= 0); gamma/beta/mean/var are DEVICE float [C].        */
+/* ------------------------------------------------------------------------- */
+int esp_dense_f32(const float *X, const float *W, float *Y,
+                  int64_t M, int64_t N, int64_t K, esp_stream stream);
+
+int esp_conv_f32(const float *in, const float *filt, float *out,
+                 int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                 esp_stream stream);
+
+int esp_bn_sign_pack_f32(const float *x, const float *gamma, const float *beta,
+                         const float *mean, const float *var, float eps,
+                         uint64_t *out, int64_t rows, int C, esp_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESPRESSO_HIP_H */

@@ -1,0 +1,266 @@
+"""Thin Python binding of the C ABI declared in ``include/espresso_hip.h``.
+
+Argument marshalling only: every function checks dtype / device / contiguity of
+its torch tensors, allocates the output tensor when none is passed, and calls
+the entry point of the same name on torch's current HIP stream.  All arithmetic
+of the method runs in the library's kernels; there is no CPU fallback -- if the
+shared library is missing, importing it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libespresso_hip.so")
+
+ESP_OK = 0
+
+EXPORTS = (
+    "esp_strerror", "esp_version", "esp_pack_f32", "esp_bgemm", "esp_unroll",
+    "esp_bconv_workspace_bytes", "esp_bconv", "esp_bn_fold", "esp_bn_sign_pack",
+    "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_sign_pack_f32",
+)
+
+_lib = None
+
+
+class EspressoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libespresso_hip.so`` (built by ``paper_1705_07175_amd.build``); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_1705_07175_amd.build`" % LIB_PATH)
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        l.esp_strerror.restype = ctypes.c_char_p
+        l.esp_strerror.argtypes = [i32]
+        l.esp_version.restype = i32
+        l.esp_pack_f32.argtypes = [vp, vp, i64, i64, vp]
+        l.esp_bgemm.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        l.esp_unroll.argtypes = [vp, vp] + [i32] * 8 + [vp]
+        l.esp_bconv_workspace_bytes.restype = ctypes.c_size_t
+        l.esp_bconv_workspace_bytes.argtypes = [i32] * 8
+        l.esp_bconv.argtypes = [vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
+        l.esp_bn_fold.argtypes = [vp, vp, vp, vp, f32, i32, vp, vp]
+        l.esp_bn_sign_pack.argtypes = [vp, vp, vp, vp, i64, i32, vp]
+        l.esp_bmaxpool.argtypes = [vp, vp] + [i32] * 6 + [vp]
+        l.esp_dense_f32.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        l.esp_conv_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+        l.esp_bn_sign_pack_f32.argtypes = [vp, vp, vp, vp, vp, f32, vp, i64, i32, vp]
+        for name in EXPORTS:
+            if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
+                getattr(l, name).restype = i32
+        _lib = l
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().esp_strerror(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().esp_version())
+
+
+def _check(status: int, where: str) -> None:
+    if status != ESP_OK:
+        raise EspressoError(status, where)
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def words(k: int) -> int:
+    """64-bit words per packed row of ``k`` values."""
+    return (int(k) + 63) // 64
+
+
+# torch has no uint64 arithmetic, and none is needed: packed buffers are int64 tensors
+# that are only ever handed to the library (same bytes as uint64).
+PACKED = torch.int64
+
+
+def pack_f32(src: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_pack_f32``: float [..., k] -> packed words [..., ceil(k/64)] (sign, Eq. 1)."""
+    p = _dev(src, torch.float32, "src")
+    k = src.shape[-1]
+    rows = src.numel() // k if k else 0
+    if out is None:
+        out = torch.empty(src.shape[:-1] + (words(k),), dtype=PACKED, device=src.device)
+    _check(lib().esp_pack_f32(p, _dev(out, PACKED, "out"), rows, k, _stream()), "esp_pack_f32")
+    return out
+
+
+def bgemm(a: torch.Tensor, b: torch.Tensor, k: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bgemm``: packed A [M][Kw], packed B [N][Kw], true length k -> int32 [M][N] (Eq. 2)."""
+    pa, pb = _dev(a, PACKED, "a"), _dev(b, PACKED, "b")
+    M, N = a.shape[0], b.shape[0]
+    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != words(k) or b.shape[1] != words(k):
+        raise ValueError("a and b must be [rows][ceil(k/64)]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _check(lib().esp_bgemm(pa, pb, _dev(out, torch.int32, "out"), M, N, int(k), _stream()), "esp_bgemm")
+    return out
+
+
+def conv_out(h: int, k: int, stride: int, pad: int) -> int:
+    return (h + 2 * pad - k) // stride + 1
+
+
+def unroll(x: torch.Tensor, c: int, kh: int, kw: int, stride: int, pad: int,
+           out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_unroll``: packed NHWC [B][H][W][Cw] -> lowered matrix [B*H2*W2][kh*kw*Cw] (Fig. 3)."""
+    p = _dev(x, PACKED, "x")
+    B, H, W, Cw = x.shape
+    if Cw != words(c):
+        raise ValueError("last dim must be ceil(c/64)")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if out is None:
+        out = torch.empty((B * max(H2, 0) * max(W2, 0), kh * kw * Cw), dtype=PACKED, device=x.device)
+    _check(lib().esp_unroll(p, _dev(out, PACKED, "out"), B, H, W, int(c), kh, kw, stride, pad, _stream()),
+           "esp_unroll")
+    return out
+
+
+def bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad) -> int:
+    return int(lib().esp_bconv_workspace_bytes(B, H, W, int(c), kh, kw, stride, pad))
+
+
+def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
+          workspace: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bconv``: packed NHWC x, packed filters [L2][kh][kw][Cw] -> int32 [B][H2][W2][L2]."""
+    px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
+    B, H, W, Cw = x.shape
+    L2, kh, kw, Cw2 = filt.shape
+    if Cw != words(c) or Cw2 != Cw:
+        raise ValueError("channel words mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if workspace is None:
+        need = bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((B, max(H2, 0), max(W2, 0), L2), dtype=torch.int32, device=x.device)
+    _check(lib().esp_bconv(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
+                           _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
+           "esp_bconv")
+    return out
+
+
+def bn_fold(gamma, beta, mean, var, eps: float):
+    """``esp_bn_fold`` (host): float32 numpy parameters -> (thr int32 [C], flip uint64 [Cw])."""
+    g, b, m, v = (np.ascontiguousarray(t, dtype=np.float32) for t in (gamma, beta, mean, var))
+    C = g.shape[0]
+    thr = np.empty(C, dtype=np.int32)
+    flip = np.empty(words(C), dtype=np.uint64)
+    _check(lib().esp_bn_fold(g.ctypes.data, b.ctypes.data, m.ctypes.data, v.ctypes.data,
+                             ctypes.c_float(eps), C, thr.ctypes.data, flip.ctypes.data), "esp_bn_fold")
+    return thr, flip
+
+
+def bn_sign_pack(x: torch.Tensor, thr: torch.Tensor, flip: torch.Tensor,
+                 out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bn_sign_pack``: int32 [..., C] + folded thresholds -> packed [..., Cw]."""
+    px = _dev(x, torch.int32, "x")
+    C = x.shape[-1]
+    rows = x.numel() // C if C else 0
+    if thr.numel() != C or flip.numel() != words(C):
+        raise ValueError("thr/flip size mismatch")
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (words(C),), dtype=PACKED, device=x.device)
+    _check(lib().esp_bn_sign_pack(px, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
+                                  _dev(out, PACKED, "out"), rows, C, _stream()), "esp_bn_sign_pack")
+    return out
+
+
+def bmaxpool(x: torch.Tensor, c: int, win: int = 2, stride: int = 2,
+             out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bmaxpool``: packed NHWC -> packed NHWC, max of +-1 values as bitwise OR."""
+    p = _dev(x, PACKED, "x")
+    B, H, W, Cw = x.shape
+    if Cw != words(c):
+        raise ValueError("last dim must be ceil(c/64)")
+    H2, W2 = (H - win) // stride + 1, (W - win) // stride + 1
+    if out is None:
+        out = torch.empty((B, max(H2, 0), max(W2, 0), Cw), dtype=PACKED, device=x.device)
+    _check(lib().esp_bmaxpool(p, _dev(out, PACKED, "out"), B, H, W, int(c), win, stride, _stream()),
+           "esp_bmaxpool")
+    return out
+
+
+def dense_f32(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_dense_f32``: float [M][K] times float +-1 weights [N][K] -> float [M][N]."""
+    px, pw = _dev(x, torch.float32, "x"), _dev(w, torch.float32, "w")
+    M, K = x.shape
+    N, K2 = w.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    _check(lib().esp_dense_f32(px, pw, _dev(out, torch.float32, "out"), M, N, K, _stream()), "esp_dense_f32")
+    return out
+
+
+def conv_f32(x: torch.Tensor, filt: torch.Tensor, stride: int, pad: int,
+             out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_conv_f32``: float NHWC, float +-1 filters [L2][kh][kw][C], zero padding."""
+    px, pf = _dev(x, torch.float32, "x"), _dev(filt, torch.float32, "filt")
+    B, H, W, C = x.shape
+    L2, kh, kw, C2 = filt.shape
+    if C != C2:
+        raise ValueError("C mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if out is None:
+        out = torch.empty((B, max(H2, 0), max(W2, 0), L2), dtype=torch.float32, device=x.device)
+    _check(lib().esp_conv_f32(px, pf, _dev(out, torch.float32, "out"), B, H, W, C, L2, kh, kw, stride, pad,
+                              _stream()), "esp_conv_f32")
+    return out
+
+
+def bn_sign_pack_f32(x: torch.Tensor, gamma, beta, mean, var, eps: float,
+                     out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bn_sign_pack_f32``: float [..., C] -> batch-norm (double) -> sign -> packed [..., Cw]."""
+    px = _dev(x, torch.float32, "x")
+    C = x.shape[-1]
+    rows = x.numel() // C if C else 0
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (words(C),), dtype=PACKED, device=x.device)
+    ptrs = [_dev(t, torch.float32, n) for t, n in ((gamma, "gamma"), (beta, "beta"), (mean, "mean"), (var, "var"))]
+    for t in (gamma, beta, mean, var):
+        if t.numel() != C:
+            raise ValueError("batch-norm parameter size mismatch")
+    _check(lib().esp_bn_sign_pack_f32(px, *ptrs, ctypes.c_float(eps), _dev(out, PACKED, "out"), rows, C,
+                                      _stream()), "esp_bn_sign_pack_f32")
+    return out
+
+
+# ------------------------------------------------------------------ host <-> device helpers
+def to_packed_tensor(words_np: np.ndarray, device="cuda") -> torch.Tensor:
+    """uint64 numpy words -> device tensor of the same bytes."""
+    return torch.from_numpy(np.ascontiguousarray(words_np, dtype=np.uint64).view(np.int64)).to(device)
+
+
+def packed_to_numpy(t: torch.Tensor) -> np.ndarray:
+    """Packed device tensor -> uint64 numpy words."""
+    return t.cpu().numpy().view(np.uint64)

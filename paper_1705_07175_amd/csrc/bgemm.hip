@@ -1,0 +1,377 @@
+// Binary matrix product on packed words (Sec. 4.2, Eq. 2 of arXiv 1705.07175):
+//   C[m][n] = K - 2 * sum_w popcount(A[m][w] XOR B[n][w]).
+//
+// Two kernels:
+//  * bgemm_tile_kernel  -- compute-bound case.  A block stages BM x 1024-bit and
+//    BN x 1024-bit slabs of the packed rows in LDS as 16-byte k-groups, every lane
+//    keeps a TM x TN tile of int32 mismatch counters in registers and runs a pure
+//    v_xor_b32 / v_bcnt_u32_b32 (accumulating popcount) inner loop on 32-bit halves
+//    of the words.  The paper's own design (shared-memory tiles + register blocking,
+//    Sec. 5.2 "Efficient Matrix multiplication") is kept; tile shapes, the LDS
+//    layout and the block order are chosen for 64-wide wavefronts and 8 XCDs.
+//  * bgemv_kernel       -- small M (matrix-vector, Sec. 6.2 "Optimized kernels"):
+//    bandwidth-bound streaming of B with the few A rows held in LDS.
+#include "esp_internal.h"
+
+namespace esp {
+
+// ---------------------------------------------------------------------------------
+// Tiled kernel
+// ---------------------------------------------------------------------------------
+constexpr int kKG = 8;        // 16-byte k-groups per LDS stage: 8 * 128 bits = 1024 bits of K
+constexpr int kStageDw = 32;  // dwords of K per row per stage
+constexpr int kXcd = 8;       // XCDs (one L2 each); blocks are dealt to them round-robin
+constexpr int kGroupM = 8;    // tile rows walked together so A and B slabs stay in one L2
+
+template <int BM, int BN, int TM, int TN, bool VEC16>
+__global__ __launch_bounds__((BM / TM) * (BN / TN))
+void bgemm_tile_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B,
+                       int32_t *__restrict__ C, int M, int N, int K_true, int row_dw,
+                       int tiles_m, int tiles_n, int tiles_per_xcd, int vec_store)
+{
+    constexpr int TX = BN / TN;      // threads along N
+    constexpr int TY = BM / TM;      // threads along M
+    constexpr int NT = TX * TY;
+    static_assert(TN % 4 == 0, "columns are owned in groups of four");
+    static_assert((BM * kKG) % NT == 0 && (BN * kKG) % NT == 0, "loader shape");
+
+    __shared__ uint4 As[kKG][BM + 1];
+    __shared__ uint4 Bs[kKG][BN + 1];
+
+    // Block -> tile: consecutive block ids land on different XCDs, so give every XCD
+    // a contiguous range of tiles and walk it in groups of kGroupM tile rows.
+    const int total_tiles = tiles_m * tiles_n;
+    const int pid = blockIdx.x;
+    const int tile = (pid % kXcd) * tiles_per_xcd + pid / kXcd;
+    if (tile >= total_tiles)
+        return;
+    const int group_size = kGroupM * tiles_n;
+    const int first_m = (tile / group_size) * kGroupM;
+    const int gm = min(tiles_m - first_m, kGroupM);
+    const int in_group = tile % group_size;
+    const int tm = first_m + in_group % gm;
+    const int tn = in_group / gm;
+    const int m0 = tm * BM;
+    const int n0 = tn * BN;
+
+    const int tid = threadIdx.x;
+    const int tx = tid % TX;
+    const int ty = tid / TX;
+
+    constexpr int A_CH = BM * kKG / NT;
+    constexpr int B_CH = BN * kKG / NT;
+    uint4 pa[A_CH], pb[B_CH];
+
+    auto fetch = [&](const uint32_t *__restrict__ base, int row, int rows, int kd) -> uint4 {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < rows) {
+            const uint32_t *p = base + (int64_t)row * row_dw + kd;
+            if (VEC16) {
+                if (kd < row_dw)
+                    v = *reinterpret_cast<const uint4 *>(p);
+            } else {
+                if (kd < row_dw) {
+                    const uint2 lo = *reinterpret_cast<const uint2 *>(p);
+                    v.x = lo.x;
+                    v.y = lo.y;
+                }
+                if (kd + 2 < row_dw) {
+                    const uint2 hi = *reinterpret_cast<const uint2 *>(p + 2);
+                    v.z = hi.x;
+                    v.w = hi.y;
+                }
+            }
+        }
+        return v;
+    };
+
+    auto prefetch = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int idx = tid + i * NT;
+            pa[i] = fetch(A, m0 + idx / kKG, M, stage * kStageDw + (idx % kKG) * 4);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int idx = tid + i * NT;
+            pb[i] = fetch(B, n0 + idx / kKG, N, stage * kStageDw + (idx % kKG) * 4);
+        }
+    };
+
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int idx = tid + i * NT;
+            As[idx % kKG][idx / kKG] = pa[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int idx = tid + i * NT;
+            const int nl = idx / kKG;
+            // column nl is register column j of lane tx: nl = (j/4)*(4*TX) + tx*4 + j%4
+            const int j = (nl / (4 * TX)) * 4 + nl % 4;
+            Bs[idx % kKG][j * TX + (nl % (4 * TX)) / 4] = pb[i];
+        }
+    };
+
+    int acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            acc[i][j] = 0;
+
+    const int stages = (row_dw + kStageDw - 1) / kStageDw;
+    prefetch(0);
+    for (int s = 0; s < stages; ++s) {
+        commit();
+        __syncthreads();
+        if (s + 1 < stages)
+            prefetch(s + 1);
+        const int left_dw = row_dw - s * kStageDw;
+        const int kgs = left_dw >= kStageDw ? kKG : (left_dw + 3) / 4;
+#pragma unroll 2
+        for (int kg = 0; kg < kgs; ++kg) {
+            uint4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = As[kg][ty + TY * i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b[j] = Bs[kg][j * TX + tx];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    acc[i][j] += __popc(a[i].x ^ b[j].x);
+                    acc[i][j] += __popc(a[i].y ^ b[j].y);
+                    acc[i][j] += __popc(a[i].z ^ b[j].z);
+                    acc[i][j] += __popc(a[i].w ^ b[j].w);
+                }
+        }
+        __syncthreads();
+    }
+
+    // Epilogue: dot = K - 2 * mismatches; each lane owns runs of four consecutive columns.
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = m0 + ty + TY * i;
+        if (row >= M)
+            continue;
+        int32_t *crow = C + (int64_t)row * N;
+#pragma unroll
+        for (int jg = 0; jg < TN / 4; ++jg) {
+            const int col = n0 + jg * 4 * TX + tx * 4;
+            int4 v;
+            v.x = K_true - 2 * acc[i][jg * 4 + 0];
+            v.y = K_true - 2 * acc[i][jg * 4 + 1];
+            v.z = K_true - 2 * acc[i][jg * 4 + 2];
+            v.w = K_true - 2 * acc[i][jg * 4 + 3];
+            if (vec_store && col + 3 < N) {
+                *reinterpret_cast<int4 *>(crow + col) = v;
+            } else {
+                if (col + 0 < N) crow[col + 0] = v.x;
+                if (col + 1 < N) crow[col + 1] = v.y;
+                if (col + 2 < N) crow[col + 2] = v.z;
+                if (col + 3 < N) crow[col + 3] = v.w;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int TM, int TN>
+static int launch_tile(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_words, hipStream_t stream)
+{
+    const int tiles_m = (int)ceil_div(M, BM);
+    const int tiles_n = (int)ceil_div(N, BN);
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    if (total > (1ll << 30))
+        return ESP_ESHAPE;
+    const int per_xcd = (int)ceil_div(total, kXcd);
+    const dim3 grid((unsigned)(per_xcd * kXcd));
+    const dim3 block((BM / TM) * (BN / TN));
+    const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
+    const int vec_store = (N % 4 == 0) && aligned(C, 16);
+    const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
+    const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
+    if (vec16)
+        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, true>), grid, block, 0, stream, a, b, C,
+                           (int)M, (int)N, (int)K_true, (int)(row_words * 2), tiles_m, tiles_n,
+                           per_xcd, vec_store);
+    else
+        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, false>), grid, block, 0, stream, a, b, C,
+                           (int)M, (int)N, (int)K_true, (int)(row_words * 2), tiles_m, tiles_n,
+                           per_xcd, vec_store);
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------------
+// Small-M kernel: stream B once, A (at most MS rows) sits in LDS.
+// A wave splits into 64/LPR groups of LPR lanes; each group owns one row of B at a
+// time, its lanes stride over the row's chunks, and a butterfly over the group's lanes
+// sums the per-lane mismatch counts.
+// ---------------------------------------------------------------------------------
+template <bool VEC16> struct Chunk;
+template <> struct Chunk<true> {
+    using type = uint4;
+    static constexpr int words = 2;
+    static __device__ __forceinline__ int mism(const uint4 a, const uint4 b)
+    {
+        return __popc(a.x ^ b.x) + __popc(a.y ^ b.y) + __popc(a.z ^ b.z) + __popc(a.w ^ b.w);
+    }
+    static __device__ __forceinline__ uint4 zero() { return make_uint4(0u, 0u, 0u, 0u); }
+};
+template <> struct Chunk<false> {
+    using type = uint2;
+    static constexpr int words = 1;
+    static __device__ __forceinline__ int mism(const uint2 a, const uint2 b)
+    {
+        return __popc(a.x ^ b.x) + __popc(a.y ^ b.y);
+    }
+    static __device__ __forceinline__ uint2 zero() { return make_uint2(0u, 0u); }
+};
+
+template <int MS, bool VEC16, bool A_LDS>
+__global__ __launch_bounds__(256)
+void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B,
+                  int32_t *__restrict__ C, int M, int N, int K_true, int row_words, int lpr)
+{
+    using CK = Chunk<VEC16>;
+    using chunk_t = typename CK::type;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    chunk_t *As = reinterpret_cast<chunk_t *>(smem_raw);
+
+    const int nch = row_words / CK::words;
+    const chunk_t *Ag = reinterpret_cast<const chunk_t *>(A);
+    const chunk_t *Bg = reinterpret_cast<const chunk_t *>(B);
+
+    if (A_LDS) {
+        for (int i = threadIdx.x; i < MS * nch; i += blockDim.x)
+            As[i] = (i / nch < M) ? Ag[i] : CK::zero();
+        __syncthreads();
+    }
+
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int waves_per_block = blockDim.x / kWave;
+    const int rpw = kWave / lpr;          // rows of B per wave pass
+    const int sub = lane / lpr;           // which of those rows this lane works on
+    const int cl = lane % lpr;            // lane index within the row group
+    const int64_t total_waves = (int64_t)gridDim.x * waves_per_block;
+    const int64_t groups = ((int64_t)N + rpw - 1) / rpw;
+
+    for (int64_t g = (int64_t)blockIdx.x * waves_per_block + wave; g < groups; g += total_waves) {
+        const int64_t row = g * rpw + sub;
+        const bool valid = row < N;
+        int acc[MS];
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+            acc[m] = 0;
+        const chunk_t *brow = Bg + row * nch;
+        int c = cl;
+        // two chunks per trip keep more loads in flight
+        for (; c + lpr < nch; c += 2 * lpr) {
+            const chunk_t b0 = valid ? brow[c] : CK::zero();
+            const chunk_t b1 = valid ? brow[c + lpr] : CK::zero();
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                const chunk_t a0 = A_LDS ? As[m * nch + c] : (m < M ? Ag[m * nch + c] : CK::zero());
+                const chunk_t a1 = A_LDS ? As[m * nch + c + lpr]
+                                         : (m < M ? Ag[m * nch + c + lpr] : CK::zero());
+                acc[m] += CK::mism(a0, b0) + CK::mism(a1, b1);
+            }
+        }
+        if (c < nch) {
+            const chunk_t b0 = valid ? brow[c] : CK::zero();
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                const chunk_t a0 = A_LDS ? As[m * nch + c] : (m < M ? Ag[m * nch + c] : CK::zero());
+                acc[m] += CK::mism(a0, b0);
+            }
+        }
+        for (int off = lpr >> 1; off > 0; off >>= 1) {
+#pragma unroll
+            for (int m = 0; m < MS; ++m)
+                acc[m] += __shfl_xor(acc[m], off, kWave);
+        }
+        if (valid && cl == 0) {
+#pragma unroll
+            for (int m = 0; m < MS; ++m)
+                if (m < M)
+                    C[(int64_t)m * N + row] = K_true - 2 * acc[m];
+        }
+    }
+}
+
+constexpr size_t kGemvLdsBytes = 64 * 1024;
+
+template <int MS, bool VEC16>
+static int launch_gemv2(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
+                        int64_t K_true, int64_t row_words, hipStream_t stream)
+{
+    const int nch = (int)(row_words / (VEC16 ? 2 : 1));
+    int lpr = 1;
+    while (lpr < kWave && lpr < nch)
+        lpr <<= 1;
+    const int rpw = kWave / lpr;
+    const int64_t groups = ceil_div(N, rpw);
+    const unsigned grid = grid_for(groups, 4 /* waves per block */, 256 * 8);
+    const size_t lds = (size_t)MS * row_words * 8;
+    if (lds <= kGemvLdsBytes)
+        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, true>), dim3(grid), dim3(256), lds, stream, A, B, C,
+                           (int)M, (int)N, (int)K_true, (int)row_words, lpr);
+    else
+        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, false>), dim3(grid), dim3(256), 0, stream, A, B, C,
+                           (int)M, (int)N, (int)K_true, (int)row_words, lpr);
+    return launch_status();
+}
+
+template <int MS>
+static int launch_gemv(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_words, hipStream_t stream)
+{
+    const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
+    return vec16 ? launch_gemv2<MS, true>(A, B, C, M, N, K_true, row_words, stream)
+                 : launch_gemv2<MS, false>(A, B, C, M, N, K_true, row_words, stream);
+}
+
+int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
+                 int64_t K_true, int64_t row_words, hipStream_t stream)
+{
+    if (M == 0)
+        return ESP_OK;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29))
+        return ESP_ESHAPE;
+    if (M <= 1)
+        return launch_gemv<1>(A, B, C, M, N, K_true, row_words, stream);
+    if (M <= 2)
+        return launch_gemv<2>(A, B, C, M, N, K_true, row_words, stream);
+    if (M <= 4)
+        return launch_gemv<4>(A, B, C, M, N, K_true, row_words, stream);
+    if (M <= 8)
+        return launch_gemv<8>(A, B, C, M, N, K_true, row_words, stream);
+    const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
+    if (big_tiles >= 512)
+        return launch_tile<128, 128, 8, 8>(A, B, C, M, N, K_true, row_words, stream);
+    return launch_tile<64, 64, 4, 4>(A, B, C, M, N, K_true, row_words, stream);
+}
+
+} // namespace esp
+
+extern "C" int esp_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C,
+                         int64_t M, int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (K >= kMaxK)
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!A || !B || !C)
+        return ESP_EINVAL;
+    if (!aligned(A, 8) || !aligned(B, 8) || !aligned(C, 4))
+        return ESP_EALIGN;
+    return bgemm_launch(A, B, C, M, N, K, ceil_div(K, 64), as_stream(stream));
+}

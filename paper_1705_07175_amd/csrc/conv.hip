@@ -1,0 +1,227 @@
+// Packed unrolling (im2col), binary convolution and OR max-pooling on channel-packed
+// NHWC tensors (arXiv 1705.07175, Sec. 5.2 "Convolutional layers", Fig. 3, and
+// "Zero-padding for convolutions").
+//
+// Because tensors are packed along channels (Sec. 5.1), every tap of a sliding volume is
+// a contiguous run of Cw words of the input pixel, so unrolling is a gather of whole
+// words: no bit moves.  Taps outside the image become zero words (= -1).
+#include "esp_internal.h"
+
+namespace esp {
+
+// One thread per VEC-word piece of the lowered matrix.  The flat piece index is split
+// into (row, tap, word) and row into (b, m, n) with multiply-shift divisions.
+template <int VEC>
+__global__ __launch_bounds__(256)
+void unroll_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
+                   uint32_t total_pieces, int H, int W, int cwv /* Cw / VEC */, int kw,
+                   int stride, int pad, FastDiv d_rowlen, FastDiv d_cwv, FastDiv d_kw,
+                   FastDiv d_w2, FastDiv d_h2)
+{
+    struct alignas(8 * VEC) piece_t { uint64_t w[VEC]; };
+    const piece_t *src = reinterpret_cast<const piece_t *>(in);
+    piece_t *dst = reinterpret_cast<piece_t *>(out);
+
+    const uint32_t stride_all = gridDim.x * blockDim.x;
+    for (uint32_t o = blockIdx.x * blockDim.x + threadIdx.x; o < total_pieces; o += stride_all) {
+        const uint32_t row = fd_div(o, d_rowlen);
+        const uint32_t j = o - row * d_rowlen.div;       // piece within the lowered row
+        const uint32_t tap = fd_div(j, d_cwv);
+        const uint32_t w = j - tap * d_cwv.div;
+        const uint32_t dy = fd_div(tap, d_kw);
+        const uint32_t dx = tap - dy * d_kw.div;
+        const uint32_t bm = fd_div(row, d_w2);
+        const uint32_t n = row - bm * d_w2.div;
+        const uint32_t b = fd_div(bm, d_h2);
+        const uint32_t m = bm - b * d_h2.div;
+        const int y = (int)(m * stride + dy) - pad;
+        const int x = (int)(n * stride + dx) - pad;
+        piece_t v;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            v.w[i] = 0;
+        if (y >= 0 && y < H && x >= 0 && x < W)
+            v = src[(((int64_t)b * H + y) * W + x) * cwv + w];
+        dst[o] = v;
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256)
+void bmaxpool_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
+                     uint32_t total_pieces, int H, int W, int cwv, int win, int stride,
+                     FastDiv d_cwv, FastDiv d_w2, FastDiv d_h2)
+{
+    struct alignas(8 * VEC) piece_t { uint64_t w[VEC]; };
+    const piece_t *src = reinterpret_cast<const piece_t *>(in);
+    piece_t *dst = reinterpret_cast<piece_t *>(out);
+
+    const uint32_t stride_all = gridDim.x * blockDim.x;
+    for (uint32_t o = blockIdx.x * blockDim.x + threadIdx.x; o < total_pieces; o += stride_all) {
+        const uint32_t pix = fd_div(o, d_cwv);
+        const uint32_t w = o - pix * d_cwv.div;
+        const uint32_t bm = fd_div(pix, d_w2);
+        const uint32_t n = pix - bm * d_w2.div;
+        const uint32_t b = fd_div(bm, d_h2);
+        const uint32_t m = bm - b * d_h2.div;
+        piece_t acc;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            acc.w[i] = 0;
+        for (int dy = 0; dy < win; ++dy)
+            for (int dx = 0; dx < win; ++dx) {
+                const int64_t y = (int64_t)m * stride + dy;
+                const int64_t x = (int64_t)n * stride + dx;
+                const piece_t v = src[(((int64_t)b * H + y) * W + x) * cwv + w];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    acc.w[i] |= v.w[i]; // max of +-1 values == OR of their sign bits
+            }
+        dst[o] = acc;
+    }
+}
+
+static bool conv_shape_ok(int B, int H, int W, int C, int kh, int kw, int stride, int pad,
+                          int64_t *H2, int64_t *W2)
+{
+    if (stride < 1 || pad < 0)
+        return false;
+    if ((int64_t)H + 2 * (int64_t)pad < kh || (int64_t)W + 2 * (int64_t)pad < kw)
+        return false;
+    *H2 = ((int64_t)H + 2 * pad - kh) / stride + 1;
+    *W2 = ((int64_t)W + 2 * pad - kw) / stride + 1;
+    (void)B;
+    (void)C;
+    return true;
+}
+
+static int unroll_launch(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
+                         int kh, int kw, int stride, int pad, hipStream_t stream)
+{
+    int64_t H2, W2;
+    if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return ESP_ESHAPE;
+    const int64_t Cw = ceil_div(C, 64);
+    const int64_t rows = (int64_t)B * H2 * W2;
+    const int64_t total_words = rows * kh * kw * Cw;
+    if (total_words >= (1ll << 31) || rows >= (1ll << 31))
+        return ESP_ESHAPE;
+    const bool vec2 = (Cw % 2 == 0) && aligned(in, 16) && aligned(out, 16);
+    const int vec = vec2 ? 2 : 1;
+    const uint32_t cwv = (uint32_t)(Cw / vec);
+    const uint32_t pieces = (uint32_t)(total_words / vec);
+    const FastDiv d_rowlen = make_fastdiv((uint32_t)(kh * kw) * cwv);
+    const FastDiv d_cwv = make_fastdiv(cwv);
+    const FastDiv d_kw = make_fastdiv((uint32_t)kw);
+    const FastDiv d_w2 = make_fastdiv((uint32_t)W2);
+    const FastDiv d_h2 = make_fastdiv((uint32_t)H2);
+    const unsigned grid = grid_for(pieces, 256);
+    if (vec2)
+        hipLaunchKernelGGL((unroll_kernel<2>), dim3(grid), dim3(256), 0, stream, in, out, pieces, H, W,
+                           (int)cwv, kw, stride, pad, d_rowlen, d_cwv, d_kw, d_w2, d_h2);
+    else
+        hipLaunchKernelGGL((unroll_kernel<1>), dim3(grid), dim3(256), 0, stream, in, out, pieces, H, W,
+                           (int)cwv, kw, stride, pad, d_rowlen, d_cwv, d_kw, d_w2, d_h2);
+    return launch_status();
+}
+
+} // namespace esp
+
+extern "C" int esp_unroll(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
+                          int kh, int kw, int stride, int pad, esp_stream stream)
+{
+    using namespace esp;
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0)
+        return ESP_EINVAL;
+    int64_t H2, W2;
+    if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return ESP_ESHAPE;
+    if (B == 0)
+        return ESP_OK;
+    if (!in || !out)
+        return ESP_EINVAL;
+    if (!aligned(in, 8) || !aligned(out, 8))
+        return ESP_EALIGN;
+    return unroll_launch(in, out, B, H, W, C, kh, kw, stride, pad, as_stream(stream));
+}
+
+extern "C" size_t esp_bconv_workspace_bytes(int B, int H, int W, int C, int kh, int kw, int stride, int pad)
+{
+    using namespace esp;
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0)
+        return 0;
+    int64_t H2, W2;
+    if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return 0;
+    return (size_t)((int64_t)B * H2 * W2 * kh * kw * ceil_div(C, 64) * 8);
+}
+
+extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                         int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                         void *workspace, size_t workspace_bytes, esp_stream stream)
+{
+    using namespace esp;
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
+        return ESP_EINVAL;
+    int64_t H2, W2;
+    if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return ESP_ESHAPE;
+    const int64_t K_true = (int64_t)kh * kw * C;
+    if (K_true >= kMaxK)
+        return ESP_ESHAPE;
+    if (B == 0)
+        return ESP_OK;
+    if (!in || !filt || !out)
+        return ESP_EINVAL;
+    if (!aligned(in, 8) || !aligned(filt, 8) || !aligned(out, 4))
+        return ESP_EALIGN;
+    const size_t need = esp_bconv_workspace_bytes(B, H, W, C, kh, kw, stride, pad);
+    if (!workspace || workspace_bytes < need)
+        return ESP_EWORKSPACE;
+    if (!aligned(workspace, 16))
+        return ESP_EALIGN;
+    uint64_t *lowered = reinterpret_cast<uint64_t *>(workspace);
+    int st = unroll_launch(in, lowered, B, H, W, C, kh, kw, stride, pad, as_stream(stream));
+    if (st != ESP_OK)
+        return st;
+    const int64_t row_words = (int64_t)kh * kw * ceil_div(C, 64);
+    return bgemm_launch(lowered, filt, out, (int64_t)B * H2 * W2, L2, K_true, row_words,
+                        as_stream(stream));
+}
+
+extern "C" int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
+                            int win, int stride, esp_stream stream)
+{
+    using namespace esp;
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || win <= 0)
+        return ESP_EINVAL;
+    if (stride < 1 || win > H || win > W)
+        return ESP_ESHAPE;
+    if (B == 0)
+        return ESP_OK;
+    if (!in || !out)
+        return ESP_EINVAL;
+    if (!aligned(in, 8) || !aligned(out, 8))
+        return ESP_EALIGN;
+    const int64_t H2 = (H - win) / stride + 1;
+    const int64_t W2 = (W - win) / stride + 1;
+    const int64_t Cw = ceil_div(C, 64);
+    const int64_t total_words = (int64_t)B * H2 * W2 * Cw;
+    if (total_words >= (1ll << 31))
+        return ESP_ESHAPE;
+    const bool vec2 = (Cw % 2 == 0) && aligned(in, 16) && aligned(out, 16);
+    const int vec = vec2 ? 2 : 1;
+    const uint32_t cwv = (uint32_t)(Cw / vec);
+    const uint32_t pieces = (uint32_t)(total_words / vec);
+    const FastDiv d_cwv = make_fastdiv(cwv);
+    const FastDiv d_w2 = make_fastdiv((uint32_t)W2);
+    const FastDiv d_h2 = make_fastdiv((uint32_t)H2);
+    const unsigned grid = grid_for(pieces, 256);
+    if (vec2)
+        hipLaunchKernelGGL((bmaxpool_kernel<2>), dim3(grid), dim3(256), 0, as_stream(stream), in, out,
+                           pieces, H, W, (int)cwv, win, stride, d_cwv, d_w2, d_h2);
+    else
+        hipLaunchKernelGGL((bmaxpool_kernel<1>), dim3(grid), dim3(256), 0, as_stream(stream), in, out,
+                           pieces, H, W, (int)cwv, win, stride, d_cwv, d_w2, d_h2);
+    return launch_status();
+}

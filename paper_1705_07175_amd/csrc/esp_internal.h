@@ -1,0 +1,74 @@
+// Internal helpers shared by the kernels of the gfx950 binary-network library.
+// Nothing here is part of the C ABI (see include/espresso_hip.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "espresso_hip.h"
+
+namespace esp {
+
+constexpr int kWave = 64;            // gfx950 wavefront size
+constexpr int64_t kMaxK = 1ll << 30; // |dot| <= K must fit int32 with headroom
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline hipStream_t as_stream(esp_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Status of the launch that was just enqueued.
+inline int launch_status() { return hipGetLastError() == hipSuccess ? ESP_OK : ESP_ELAUNCH; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Division of a 32-bit unsigned value by a run-time constant, done as a
+// multiply-high and a shift (round-up method, exact for n < 2^31).
+struct FastDiv {
+    uint32_t mul;
+    uint32_t shift;
+    uint32_t div;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.div = d;
+    if (d == 1) {
+        f.mul = 0;
+        f.shift = 0;
+        return f;
+    }
+    uint32_t l = 0;
+    while ((1ull << l) < d)
+        ++l; // l = ceil(log2 d)
+    const uint64_t m = ((1ull << (31 + l)) + d - 1) / d;
+    f.mul = static_cast<uint32_t>(m);
+    f.shift = l - 1;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fd_div(uint32_t n, const FastDiv f)
+{
+    // mul = ceil(2^(31+l) / d) with l = ceil(log2 d): (n * mul) >> (31 + l) == n / d for n < 2^31.
+    return f.div == 1 ? n : (__umulhi(n, f.mul) >> f.shift);
+}
+
+// Number of blocks for a grid-stride kernel: enough to fill 256 CUs several
+// times over without creating millions of tiny blocks.
+inline unsigned grid_for(int64_t work_items, int per_block, int max_blocks = 256 * 32)
+{
+    int64_t b = ceil_div(work_items, per_block);
+    if (b < 1)
+        b = 1;
+    if (b > max_blocks)
+        b = max_blocks;
+    return static_cast<unsigned>(b);
+}
+
+// bgemm on raw word rows whose stored width (row pitch in uint64 words) is
+// given separately from the true bit length K: the lowered matrix of a
+// convolution pads every tap to whole words, so its pitch is not ceil(K/64).
+int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
+                 int64_t K_true, int64_t row_words, hipStream_t stream);
+
+} // namespace esp

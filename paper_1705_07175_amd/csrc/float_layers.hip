@@ -1,0 +1,201 @@
+// Real-valued first layer in fp32 (the non-binary variant of a layer, Sec. 3 of
+// arXiv 1705.07175): the networks of Sec. 6.2 / 6.3 start from real-valued images, so
+// their first dense / convolutional layer multiplies floats by +-1 weights.  These are
+// supporting kernels, kept simple: an LDS-tiled SGEMM, a wave-per-output GEMV for tiny
+// batches and a direct convolution with the filters transposed in LDS.
+#include "esp_internal.h"
+
+namespace esp {
+
+// Y[M][N] = X[M][K] * W[N][K]^T, 64x64 tile, 256 threads, 4x4 outputs per thread.
+__global__ __launch_bounds__(256)
+void dense_f32_tile_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
+                           float *__restrict__ Y, int M, int N, int K)
+{
+    constexpr int BT = 64, BK = 16;
+    __shared__ float Xs[BK][BT + 4];
+    __shared__ float Ws[BK][BT + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid % 16, ty = tid / 16;
+    const int m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        // 64 rows x 16 k per operand = 1024 values, 4 per thread; k fastest so that a
+        // group of 16 lanes reads 64 contiguous bytes of one row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + i * 256;
+            const int r = idx / BK, k = idx % BK;
+            const bool kin = k0 + k < K;
+            Xs[k][r] = (kin && m0 + r < M) ? X[(int64_t)(m0 + r) * K + k0 + k] : 0.0f;
+            Ws[k][r] = (kin && n0 + r < N) ? Wt[(int64_t)(n0 + r) * K + k0 + k] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < BK; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = Xs[k][ty + 16 * i];
+                b[i] = Ws[k][tx + 16 * i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty + 16 * i;
+        if (m >= M)
+            continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx + 16 * j;
+            if (n < N)
+                Y[(int64_t)m * N + n] = acc[i][j];
+        }
+    }
+}
+
+// Small batch: one wave per output neuron n, lanes stride over K, all (<= 4) rows of X
+// reuse each weight load; butterfly sum at the end.
+template <int MS>
+__global__ __launch_bounds__(256)
+void dense_f32_gemv_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
+                           float *__restrict__ Y, int M, int N, int K)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t n = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (n >= N)
+        return;
+    float acc[MS];
+#pragma unroll
+    for (int m = 0; m < MS; ++m)
+        acc[m] = 0.0f;
+    const float *wrow = Wt + n * K;
+    for (int k = lane; k < K; k += kWave) {
+        const float w = wrow[k];
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+            if (m < M)
+                acc[m] = fmaf(X[(int64_t)m * K + k], w, acc[m]);
+    }
+#pragma unroll
+    for (int m = 0; m < MS; ++m) {
+        float v = acc[m];
+        for (int off = 32; off > 0; off >>= 1)
+            v += __shfl_xor(v, off, kWave);
+        if (lane == 0 && m < M)
+            Y[(int64_t)m * N + n] = v;
+    }
+}
+
+// Direct NHWC convolution, zero padding.  The block copies the filters to LDS as
+// [tap*C + c][L2] so that lanes (= output channels) read consecutive addresses, then
+// walks its share of output pixels; the input value of a tap is the same for every lane
+// of a pixel.
+__global__ __launch_bounds__(256)
+void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ filt,
+                     float *__restrict__ out, int B, int H, int W, int C, int L2, int kh, int kw,
+                     int stride, int pad, int H2, int W2, int filt_in_lds)
+{
+    extern __shared__ float fT[];
+    const int taps = kh * kw * C;
+    if (filt_in_lds) {
+        for (int i = threadIdx.x; i < taps * L2; i += blockDim.x) {
+            const int l2 = i / taps, t = i % taps;
+            fT[t * L2 + l2] = filt[i];
+        }
+        __syncthreads();
+    }
+    const int64_t total = (int64_t)B * H2 * W2 * L2;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += step) {
+        const int l2 = (int)(o % L2);
+        const int64_t pix = o / L2;
+        const int n = (int)(pix % W2);
+        const int m = (int)((pix / W2) % H2);
+        const int b = (int)(pix / ((int64_t)W2 * H2));
+        float acc = 0.0f;
+        for (int dy = 0; dy < kh; ++dy) {
+            const int y = m * stride + dy - pad;
+            if (y < 0 || y >= H)
+                continue;
+            for (int dx = 0; dx < kw; ++dx) {
+                const int x = n * stride + dx - pad;
+                if (x < 0 || x >= W)
+                    continue;
+                const float *ip = in + (((int64_t)b * H + y) * W + x) * C;
+                const int t0 = (dy * kw + dx) * C;
+                for (int c = 0; c < C; ++c) {
+                    const float f = filt_in_lds ? fT[(t0 + c) * L2 + l2] : filt[(int64_t)l2 * taps + t0 + c];
+                    acc = fmaf(ip[c], f, acc);
+                }
+            }
+        }
+        out[o] = acc;
+    }
+}
+
+} // namespace esp
+
+extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
+                             int64_t M, int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31))
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!X || !W || !Y)
+        return ESP_EINVAL;
+    if (!aligned(X, 4) || !aligned(W, 4) || !aligned(Y, 4))
+        return ESP_EALIGN;
+    hipStream_t s = as_stream(stream);
+    if (M <= 4) {
+        const dim3 grid((unsigned)ceil_div(N, 4));
+        if (M == 1)
+            hipLaunchKernelGGL((dense_f32_gemv_kernel<1>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K);
+        else
+            hipLaunchKernelGGL((dense_f32_gemv_kernel<4>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K);
+        return launch_status();
+    }
+    const int64_t gy = ceil_div(M, 64);
+    if (gy > 65535)
+        return ESP_ESHAPE;
+    const dim3 grid((unsigned)ceil_div(N, 64), (unsigned)gy);
+    hipLaunchKernelGGL(dense_f32_tile_kernel, grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K);
+    return launch_status();
+}
+
+extern "C" int esp_conv_f32(const float *in, const float *filt, float *out,
+                            int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                            esp_stream stream)
+{
+    using namespace esp;
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
+        return ESP_EINVAL;
+    if (stride < 1 || pad < 0 || (int64_t)H + 2 * (int64_t)pad < kh || (int64_t)W + 2 * (int64_t)pad < kw)
+        return ESP_ESHAPE;
+    if (B == 0)
+        return ESP_OK;
+    if (!in || !filt || !out)
+        return ESP_EINVAL;
+    if (!aligned(in, 4) || !aligned(filt, 4) || !aligned(out, 4))
+        return ESP_EALIGN;
+    const int H2 = (H + 2 * pad - kh) / stride + 1;
+    const int W2 = (W + 2 * pad - kw) / stride + 1;
+    const int64_t total = (int64_t)B * H2 * W2 * L2;
+    const size_t lds = (size_t)kh * kw * C * L2 * sizeof(float);
+    const int in_lds = lds <= 48 * 1024;
+    const unsigned grid = grid_for(total, 256 * 8);
+    hipLaunchKernelGGL(conv_f32_kernel, dim3(grid), dim3(256), in_lds ? lds : 0, as_stream(stream), in,
+                       filt, out, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, in_lds);
+    return launch_status();
+}

@@ -1,0 +1,148 @@
+"""Host-side drivers that chain the library calls into the two networks of the paper's
+evaluation (arXiv 1705.07175): the MNIST multi-layer perceptron of Sec. 6.2 and the
+CIFAR-10 VGG-like network of Sec. 6.3.
+
+Following the paper, weights are bit-packed once when the network is built (Sec. 6.2
+"Binary optimized layers"), batch-norm is folded to integer thresholds at the same
+time, and every activation / workspace buffer is allocated up front (Sec. 3
+"Technical highlights"): ``forward`` only enqueues kernels on the current stream, so
+it can be captured in a HIP graph.  The first layer is real-valued (fp32), all others
+are binary; the last layer returns raw int32 scores.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as esp
+
+
+def _dev_f32(a, device):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+class _FoldedBN:
+    """Batch-norm parameters: raw float (first layer) and folded integer thresholds."""
+
+    def __init__(self, bnp, eps, device, fold=True):
+        self.eps = float(eps)
+        self.raw = tuple(_dev_f32(t, device) for t in bnp)
+        if fold:
+            thr, flip = esp.bn_fold(*bnp, self.eps)
+            self.thr = torch.from_numpy(thr).to(device)
+            self.flip = esp.to_packed_tensor(flip, device)
+
+
+def _pack_weights(w_pm1: np.ndarray, device) -> torch.Tensor:
+    """+-1 weights [N][...][K] -> packed words via the library's own pack kernel."""
+    return esp.pack_f32(_dev_f32(w_pm1, device))
+
+
+class BinaryMLP:
+    """Sec. 6.2 network: float dense, then binary dense layers, BN + sign in between."""
+
+    def __init__(self, layers, batch: int, eps: float, device="cuda"):
+        self.batch = batch
+        self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
+        self.w1 = _dev_f32(layers[0]["w"], device)
+        self.bn = [_FoldedBN(l["bn"], eps, device, fold=(i > 0)) if l["bn"] is not None else None
+                   for i, l in enumerate(layers)]
+        self.wp = [None] + [_pack_weights(l["w"], device) for l in layers[1:]]
+        # pre-allocated activations
+        self.pre = [torch.empty((batch, self.sizes[1]), dtype=torch.float32, device=device)]
+        self.pre += [torch.empty((batch, n), dtype=torch.int32, device=device) for n in self.sizes[2:]]
+        self.act = [torch.empty((batch, esp.words(n)), dtype=esp.PACKED, device=device)
+                    for n in self.sizes[1:-1]]
+        torch.cuda.synchronize()
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        esp.dense_f32(x, self.w1, out=self.pre[0])
+        esp.bn_sign_pack_f32(self.pre[0], *self.bn[0].raw, self.bn[0].eps, out=self.act[0])
+        for i in range(1, len(self.wp)):
+            esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
+            if self.bn[i] is not None:
+                esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
+        return self.pre[-1]
+
+    def forward_from_first_act(self, act0: torch.Tensor) -> torch.Tensor:
+        """Binary layers only, starting from given packed first-layer activations."""
+        self.act[0].copy_(act0)
+        for i in range(1, len(self.wp)):
+            esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
+            if self.bn[i] is not None:
+                esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
+        return self.pre[-1]
+
+
+class BinaryCNN:
+    """Sec. 6.3 network: float conv, binary 3x3 convs (border = -1), OR max-pools, binary dense."""
+
+    def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda"):
+        self.batch = batch
+        self.steps = []          # one record per layer, in order
+        h = hw
+        c = layers[0]["w"].shape[3]
+        flat = None
+        ws_bytes = 16
+        for i, l in enumerate(layers):
+            kind = l["kind"]
+            rec = {"kind": kind}
+            if kind == "pool":
+                rec.update(c=c, h=h)
+                h //= 2
+                rec["out"] = torch.empty((batch, h, h, esp.words(c)), dtype=esp.PACKED, device=device)
+            elif kind == "conv":
+                l2 = l["w"].shape[0]
+                rec.update(c=c, h=h, l2=l2)
+                if i == 0:
+                    rec["w"] = _dev_f32(l["w"], device)
+                    rec["pre"] = torch.empty((batch, h, h, l2), dtype=torch.float32, device=device)
+                    rec["bn"] = _FoldedBN(l["bn"], eps, device, fold=False)
+                else:
+                    rec["w"] = _pack_weights(l["w"], device)
+                    rec["pre"] = torch.empty((batch, h, h, l2), dtype=torch.int32, device=device)
+                    rec["bn"] = _FoldedBN(l["bn"], eps, device)
+                    ws_bytes = max(ws_bytes, esp.bconv_workspace_bytes(batch, h, h, c, 3, 3, 1, 1))
+                rec["out"] = torch.empty((batch, h, h, esp.words(l2)), dtype=esp.PACKED, device=device)
+                c = l2
+            else:
+                n, k = l["w"].shape
+                if flat is None:
+                    flat = h * h * c
+                    assert flat == k, (flat, k)
+                rec.update(k=k, n=n)
+                rec["w"] = _pack_weights(l["w"], device)
+                rec["pre"] = torch.empty((batch, n), dtype=torch.int32, device=device)
+                if l["bn"] is not None:
+                    rec["bn"] = _FoldedBN(l["bn"], eps, device)
+                    rec["out"] = torch.empty((batch, esp.words(n)), dtype=esp.PACKED, device=device)
+                else:
+                    rec["bn"] = None
+            self.steps.append(rec)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
+        torch.cuda.synchronize()
+
+    def forward(self, x: torch.Tensor, first_act: torch.Tensor | None = None) -> torch.Tensor:
+        cur = None
+        for i, s in enumerate(self.steps):
+            kind = s["kind"]
+            if kind == "pool":
+                cur = esp.bmaxpool(cur, s["c"], 2, 2, out=s["out"])
+            elif kind == "conv" and i == 0:
+                if first_act is None:
+                    esp.conv_f32(x, s["w"], 1, 1, out=s["pre"])
+                    esp.bn_sign_pack_f32(s["pre"], *s["bn"].raw, s["bn"].eps, out=s["out"])
+                else:
+                    s["out"].copy_(first_act)
+                cur = s["out"]
+            elif kind == "conv":
+                esp.bconv(cur, s["w"], s["c"], 1, 1, workspace=self.workspace, out=s["pre"])
+                cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
+            else:
+                a = cur.reshape(self.batch, -1)   # flatten in storage order: free
+                esp.bgemm(a, s["w"], s["k"], out=s["pre"])
+                if s["bn"] is not None:
+                    cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
+                else:
+                    cur = s["pre"]
+        return cur

@@ -26,3 +26,18 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_libraries():
+    """Use the libraries that are built; build them only if nothing is there."""
+    from paper_1705_07175_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1705_07175_amd import build as hip_build
+
+        hip_build.build()
+    import oracle
+
+    oracle.build()
+    yield
