@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X binary-network forward path (after arXiv 1705.07175).
+
+Headline line (one JSON object on stdout): the bit-packed binary matrix product of
+Sec. 6.1 -- two dense 8192 x 8192 +-1 matrices, packed along K -- timed with HIP events
+over exactly ``--steps`` launches after ``--warmup`` untimed ones, inputs resident in
+HBM.  ``value`` is Gbop/s with 2 binary operations per multiply-accumulate.
+
+The same object carries
+  * ``roofline``      the dominant kernel (bgemm) against the integer-VALU XOR+popcount peak,
+  * ``cpu_baseline``  the CPU oracle timed on this host on a bounded sample of the same job,
+  * ``kernels``       the supporting kernels (pack, unroll, bn_sign_pack, bmaxpool, small-M
+                      bgemm) on HBM-sized inputs against the 8 TB/s HBM peak,
+  * ``networks``      images/s of the paper's MLP (Sec. 6.2) and CNN (Sec. 6.3) shapes.
+
+All inputs are seeded and synthetic (``paper_1705_07175_amd.synth``).  One GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMDs x 16 lanes, 2.4 GHz peak engine clock.
+CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
+# One v_xor_b32 + one accumulating v_bcnt_u32_b32 per lane handle 32 binary MACs = 64 bop.
+VALU_PEAK_TBOPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ * 64 / 2 / 1e12      # 1258.3 Tbop/s
+HBM_PEAK_GBS = 8000.0
+
+
+def _events_ms(fn, steps, warmup, torch):
+    """Average milliseconds per call of ``fn`` over ``steps`` calls, HIP events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(stop) / steps, wall_ms / steps
+
+
+def _hbm_entry(name, ms, algo_bytes, workload):
+    gbs = algo_bytes / (ms * 1e-3) / 1e9
+    return {"kernel": name, "workload": workload, "ms": round(ms, 5), "bound": "hbm",
+            "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": int(algo_bytes)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--size", type=int, default=8192, help="M=N=K of the headline binary GEMM")
+    ap.add_argument("--no-extras", action="store_true", help="skip supporting kernels and networks")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample rows (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1705_07175_amd import binding as esp
+    from paper_1705_07175_amd import nets, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    esp.lib()  # fails loudly if the HIP library is not built
+
+    def to_dev_f32(a):
+        return torch.from_numpy(a).to(dev).to(torch.float32)
+
+    n = args.size
+    a_pm1, b_pm1 = synth.config5_square(n)
+    a_f = to_dev_f32(a_pm1)
+    A = esp.pack_f32(a_f)
+    del a_f
+    b_f = to_dev_f32(b_pm1)
+    B = esp.pack_f32(b_f)
+    C = torch.empty((n, n), dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+
+    ms, wall_ms = _events_ms(lambda: esp.bgemm(A, B, n, out=C), args.steps, args.warmup, torch)
+    bop = 2.0 * n * n * n
+    gbops = bop / (ms * 1e-3) / 1e9
+    tbops = gbops / 1e3
+
+    # cheap full-coverage sanity check of the timed result (row checksum identity)
+    rows = np.array([0, n // 3, n - 1])
+    bsum = b_pm1.astype(np.int64).sum(axis=0)
+    got = C[torch.from_numpy(rows).to(dev)].sum(dim=1, dtype=torch.int64).cpu().numpy()
+    if not np.array_equal(got, a_pm1[rows].astype(np.int64) @ bsum):
+        print("bench.py: bgemm result failed its checksum", file=sys.stderr)
+        return 1
+
+    result = {
+        "metric": "binary GEMM Gbop/s (% of int VALU peak); BCNN images/sec at batch 1 and 256",
+        "value": round(gbops, 1),
+        "unit": "Gbop/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "wall_ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64 words (1-bit operands), int32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "config 5: binary GEMM M=N=K=%d, +-1 i.i.d., packed uint64, int32 out "
+                               "(the matrix size of Sec. 6.1, Table 1)" % n,
+                   "pct_of_int_valu_peak": round(100.0 * tbops / VALU_PEAK_TBOPS, 2)},
+        "roofline": {"bound": "alu", "kernel": "bgemm_tile_kernel", "achieved": round(tbops, 2),
+                     "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s",
+                     "frac": round(tbops / VALU_PEAK_TBOPS, 4), "traffic": None,
+                     "algorithmic_bop_per_launch": bop,
+                     "algorithmic_bytes_per_launch": 2 * n * n // 8 + 4 * n * n},
+        "paper_context": "Sec. 6.1 Table 1: 11 ms for this product on a GTX 960 (64-bit packing)",
+    }
+
+    del b_f
+    if not args.no_extras:
+        result["kernels"] = _supporting_kernels(torch, esp, synth, dev, np)
+        result["networks"] = _networks(torch, esp, nets, synth, dev)
+        cnn = result["networks"]["bcnn"]
+        result["bcnn_images_per_s"] = {"batch1": cnn["1"]["images_per_s"], "batch256": cnn["256"]["images_per_s"]}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = _cpu_baseline(a_pm1, b_pm1, n, args.cpu_rows, np)
+
+    print(json.dumps(result))
+    return 0
+
+
+def _supporting_kernels(torch, esp, synth, dev, np):
+    """Bandwidth-bound kernels on working sets far larger than the 256 MiB last-level cache."""
+    out = []
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.SEED0)
+
+    # pack: 16384 x 16384 float32 (1 GiB) -> 32 MiB of words (the largest matrix of config 5)
+    rows, k = 16384, 16384
+    x = torch.rand((rows, k), device=dev, generator=g) - 0.5
+    dst = torch.empty((rows, k // 64), dtype=esp.PACKED, device=dev)
+    ms, _ = _events_ms(lambda: esp.pack_f32(x, out=dst), 20, 3, torch)
+    out.append(_hbm_entry("pack_f32", ms, rows * k * 4 + rows * k // 8, "float32 16384x16384 -> bits"))
+    del x
+
+    # bn_sign_pack: conv-layer output shape of the CNN scaled to 1 GiB: rows x 128 channels
+    rows, c = 2 * 1024 * 1024, 128
+    xi = torch.randint(-1152, 1153, (rows, c), device=dev, generator=g, dtype=torch.int32)
+    bnp = synth.bn_params(synth.rng_for(2, 7), c)
+    thr_np, flip_np = esp.bn_fold(*bnp, synth.BN_EPS)
+    thr = torch.from_numpy(thr_np).to(dev)
+    flip = esp.to_packed_tensor(flip_np, dev)
+    dst = torch.empty((rows, c // 64), dtype=esp.PACKED, device=dev)
+    ms, _ = _events_ms(lambda: esp.bn_sign_pack(xi, thr, flip, out=dst), 20, 3, torch)
+    out.append(_hbm_entry("bn_sign_pack", ms, rows * c * 4 + rows * c // 8 + c * 4 + c // 8,
+                          "int32 [2Mi][128] -> bits (CNN conv2 output, batch 2048)"))
+    del xi
+
+    # unroll: CNN conv2 input at batch 4096: 64 MiB in -> 576 MiB lowered
+    b, h, c = 4096, 32, 128
+    xin = torch.randint(-2**62, 2**62, (b, h, h, c // 64), device=dev, generator=g, dtype=torch.int64)
+    low = torch.empty((b * h * h, 9 * c // 64), dtype=esp.PACKED, device=dev)
+    ms, _ = _events_ms(lambda: esp.unroll(xin, c, 3, 3, 1, 1, out=low), 20, 3, torch)
+    out.append(_hbm_entry("unroll", ms, xin.numel() * 8 + low.numel() * 8,
+                          "packed [4096][32][32][128] 3x3 s1 p1 -> lowered matrix"))
+    del low
+
+    # bmaxpool on a 1 GiB packed tensor
+    b, h, c = 4096, 64, 512
+    xin = torch.randint(-2**62, 2**62, (b, h, h, c // 64), device=dev, generator=g, dtype=torch.int64)
+    pooled = torch.empty((b, h // 2, h // 2, c // 64), dtype=esp.PACKED, device=dev)
+    ms, _ = _events_ms(lambda: esp.bmaxpool(xin, c, 2, 2, out=pooled), 20, 3, torch)
+    out.append(_hbm_entry("bmaxpool", ms, xin.numel() * 8 * 1.25, "packed [4096][64][64][512] 2x2 s2"))
+    del xin, pooled
+
+    # small-M bgemm (matrix-vector): config 5's batch-1 product, K = N = 16384 (B = 32 MiB,
+    # cache-resident across repeats) and a 1 GiB weight matrix that is not
+    for nrows, kk, label in ((16384, 16384, "config 5 GEMV M=1, N=K=16384 (32 MiB weights, cache-resident)"),
+                             (524288, 16384, "M=1, N=524288, K=16384 (1 GiB weights)")):
+        bw = torch.randint(-2**62, 2**62, (nrows, kk // 64), device=dev, generator=g, dtype=torch.int64)
+        av = torch.randint(-2**62, 2**62, (1, kk // 64), device=dev, generator=g, dtype=torch.int64)
+        cv = torch.empty((1, nrows), dtype=torch.int32, device=dev)
+        ms, _ = _events_ms(lambda: esp.bgemm(av, bw, kk, out=cv), 20, 3, torch)
+        e = _hbm_entry("bgemv", ms, nrows * kk // 8 + kk // 8 + nrows * 4, label)
+        e["gbops"] = round(2.0 * nrows * kk / (ms * 1e-3) / 1e9, 1)
+        out.append(e)
+        del bw
+    return out
+
+
+def _networks(torch, esp, nets, synth, dev):
+    """images/s of the two networks; batch 1 is timed both eagerly and as a replayed HIP graph."""
+    res = {"bmlp": {}, "bcnn": {}}
+
+    def time_net(net, x, batch, steps):
+        entry = {}
+        ms, wall = _events_ms(lambda: net.forward(x), steps, 3, torch)
+        entry["eager_ms"] = round(max(ms, wall), 5)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            net.forward(x)
+        ms_g, wall_g = _events_ms(graph.replay, steps, 3, torch)
+        entry["graph_ms"] = round(max(ms_g, wall_g), 5)
+        best = min(entry["eager_ms"], entry["graph_ms"])
+        entry["images_per_s"] = round(batch / (best * 1e-3), 1)
+        return entry
+
+    layers = synth.mlp_params()
+    for batch in (1, 64, 1024):
+        net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev)
+        x = torch.from_numpy(synth.mlp_input(batch)).to(dev)
+        res["bmlp"][str(batch)] = time_net(net, x, batch, 50)
+        del net
+    layers = synth.cnn_params()
+    for batch in (1, 256):
+        net = nets.BinaryCNN(layers, batch, synth.BN_EPS, device=dev)
+        x = torch.from_numpy(synth.cnn_input(batch)).to(dev)
+        res["bcnn"][str(batch)] = time_net(net, x, batch, 30)
+        del net
+    res["paper_context"] = "batch 1 on a GTX 960: BMLP 0.26 ms (Table 2), BCNN 1.0 ms (Table 3)"
+    return res
+
+
+def _cpu_baseline(a_pm1, b_pm1, n, sample_rows, np):
+    """The oracle's plain +-1 product on a sample of output rows (rows are independent),
+    all host threads, extrapolated linearly to the metric's unit."""
+    import oracle
+
+    threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
+    oracle.set_threads(threads)
+    probe = oracle.dense_pm1  # plain triple loop, int8 operands, int32 sums
+    t0 = time.perf_counter()
+    probe(a_pm1[:threads], b_pm1[: n // 8])
+    dt = max(time.perf_counter() - t0, 1e-6)
+    rate = threads * (n // 8) * n / dt                     # MAC/s estimate
+    rows = sample_rows or int(min(n, max(threads, (15.0 * rate) / (n * n))))
+    rows = max(threads, rows - rows % threads)
+    t0 = time.perf_counter()
+    probe(a_pm1[:rows], b_pm1)
+    dt = time.perf_counter() - t0
+    oracle.set_threads(1)
+    gbops = 2.0 * rows * n * n / dt / 1e9
+    return {"value": round(gbops, 2), "unit": "Gbop/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d output rows (all N, all K) of the same product, %.1f s; "
+                      "full job extrapolated linearly: %.0f s" % (rows, n, dt, 2.0 * n**3 / (gbops * 1e9))}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
