@@ -67,6 +67,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip supporting kernels and networks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample rows (0 = auto)")
+    ap.add_argument("--only", default="", help="time ONE supporting workload and print its entry "
+                    "(for profiler runs): bgemm, bcnn<batch>, bmlp<batch>, " + ", ".join(SUPPORTING))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -85,6 +87,19 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     esp.lib()  # fails loudly if the HIP library is not built
+
+    if args.only.startswith(("bcnn", "bmlp")):
+        kind, batch = args.only[:4], int(args.only[4:])
+        print(json.dumps(_networks(torch, esp, nets, synth, dev, only=(kind, batch))))
+        return 0
+    if args.only and args.only != "bgemm":
+        if args.only not in SUPPORTING:
+            print("bench.py: unknown --only %r" % args.only, file=sys.stderr)
+            return 2
+        entry = _supporting_kernels(torch, esp, synth, dev, np, only=args.only,
+                                    steps=args.steps, warmup=args.warmup)[0]
+        print(json.dumps(entry))
+        return 0
 
     def to_dev_f32(a):
         return torch.from_numpy(a).to(dev).to(torch.float32)
@@ -138,6 +153,9 @@ def main() -> int:
     }
 
     del b_f
+    if args.only == "bgemm":
+        print(json.dumps(result))
+        return 0
     if not args.no_extras:
         result["kernels"] = _supporting_kernels(torch, esp, synth, dev, np)
         result["networks"] = _networks(torch, esp, nets, synth, dev)
@@ -151,66 +169,104 @@ def main() -> int:
     return 0
 
 
-def _supporting_kernels(torch, esp, synth, dev, np):
-    """Bandwidth-bound kernels on working sets far larger than the 256 MiB last-level cache."""
+SUPPORTING = ("copy", "pack", "bn_sign_pack", "unroll", "bmaxpool", "bgemv", "bgemv_1g", "bconv_cfg2")
+
+
+def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3):
+    """Bandwidth-bound kernels on working sets far larger than the 256 MiB last-level cache,
+    plus config 2's convolution.  ``copy`` is torch's plain device copy of 1 GiB: it is not part
+    of the library and only calibrates what the profiler's byte counters read per byte moved."""
     out = []
     g = torch.Generator(device=dev)
     g.manual_seed(synth.SEED0)
 
-    # pack: 16384 x 16384 float32 (1 GiB) -> 32 MiB of words (the largest matrix of config 5)
-    rows, k = 16384, 16384
-    x = torch.rand((rows, k), device=dev, generator=g) - 0.5
-    dst = torch.empty((rows, k // 64), dtype=esp.PACKED, device=dev)
-    ms, _ = _events_ms(lambda: esp.pack_f32(x, out=dst), 20, 3, torch)
-    out.append(_hbm_entry("pack_f32", ms, rows * k * 4 + rows * k // 8, "float32 16384x16384 -> bits"))
-    del x
+    def want(name):
+        return (not only and name != "copy") or only == name
 
-    # bn_sign_pack: conv-layer output shape of the CNN scaled to 1 GiB: rows x 128 channels
-    rows, c = 2 * 1024 * 1024, 128
-    xi = torch.randint(-1152, 1153, (rows, c), device=dev, generator=g, dtype=torch.int32)
-    bnp = synth.bn_params(synth.rng_for(2, 7), c)
-    thr_np, flip_np = esp.bn_fold(*bnp, synth.BN_EPS)
-    thr = torch.from_numpy(thr_np).to(dev)
-    flip = esp.to_packed_tensor(flip_np, dev)
-    dst = torch.empty((rows, c // 64), dtype=esp.PACKED, device=dev)
-    ms, _ = _events_ms(lambda: esp.bn_sign_pack(xi, thr, flip, out=dst), 20, 3, torch)
-    out.append(_hbm_entry("bn_sign_pack", ms, rows * c * 4 + rows * c // 8 + c * 4 + c // 8,
-                          "int32 [2Mi][128] -> bits (CNN conv2 output, batch 2048)"))
-    del xi
+    def rand_words(shape):
+        return torch.randint(-2**62, 2**62, shape, device=dev, generator=g, dtype=torch.int64)
 
-    # unroll: CNN conv2 input at batch 4096: 64 MiB in -> 576 MiB lowered
-    b, h, c = 4096, 32, 128
-    xin = torch.randint(-2**62, 2**62, (b, h, h, c // 64), device=dev, generator=g, dtype=torch.int64)
-    low = torch.empty((b * h * h, 9 * c // 64), dtype=esp.PACKED, device=dev)
-    ms, _ = _events_ms(lambda: esp.unroll(xin, c, 3, 3, 1, 1, out=low), 20, 3, torch)
-    out.append(_hbm_entry("unroll", ms, xin.numel() * 8 + low.numel() * 8,
-                          "packed [4096][32][32][128] 3x3 s1 p1 -> lowered matrix"))
-    del low
+    if want("copy"):
+        src = rand_words((128 * 1024 * 1024,))
+        dst = torch.empty_like(src)
+        ms, _ = _events_ms(lambda: dst.copy_(src), steps, warmup, torch)
+        out.append(_hbm_entry("copy (torch, calibration only)", ms, 2 * src.numel() * 8, "1 GiB -> 1 GiB"))
+        del src, dst
 
-    # bmaxpool on a 1 GiB packed tensor
-    b, h, c = 4096, 64, 512
-    xin = torch.randint(-2**62, 2**62, (b, h, h, c // 64), device=dev, generator=g, dtype=torch.int64)
-    pooled = torch.empty((b, h // 2, h // 2, c // 64), dtype=esp.PACKED, device=dev)
-    ms, _ = _events_ms(lambda: esp.bmaxpool(xin, c, 2, 2, out=pooled), 20, 3, torch)
-    out.append(_hbm_entry("bmaxpool", ms, xin.numel() * 8 * 1.25, "packed [4096][64][64][512] 2x2 s2"))
-    del xin, pooled
+    if want("pack"):
+        # 16384 x 16384 float32 (1 GiB) -> 32 MiB of words (the largest matrix of config 5)
+        rows, k = 16384, 16384
+        x = torch.rand((rows, k), device=dev, generator=g) - 0.5
+        dst = torch.empty((rows, k // 64), dtype=esp.PACKED, device=dev)
+        ms, _ = _events_ms(lambda: esp.pack_f32(x, out=dst), steps, warmup, torch)
+        out.append(_hbm_entry("pack_f32", ms, rows * k * 4 + rows * k // 8, "float32 16384x16384 -> bits"))
+        del x, dst
 
-    # small-M bgemm (matrix-vector): config 5's batch-1 product, K = N = 16384 (B = 32 MiB,
-    # cache-resident across repeats) and a 1 GiB weight matrix that is not
-    for nrows, kk, label in ((16384, 16384, "config 5 GEMV M=1, N=K=16384 (32 MiB weights, cache-resident)"),
-                             (524288, 16384, "M=1, N=524288, K=16384 (1 GiB weights)")):
-        bw = torch.randint(-2**62, 2**62, (nrows, kk // 64), device=dev, generator=g, dtype=torch.int64)
-        av = torch.randint(-2**62, 2**62, (1, kk // 64), device=dev, generator=g, dtype=torch.int64)
+    if want("bn_sign_pack"):
+        # conv-layer output of the CNN scaled to 1 GiB: rows x 128 channels
+        rows, c = 2 * 1024 * 1024, 128
+        xi = torch.randint(-1152, 1153, (rows, c), device=dev, generator=g, dtype=torch.int32)
+        bnp = synth.bn_params(synth.rng_for(2, 7), c)
+        thr_np, flip_np = esp.bn_fold(*bnp, synth.BN_EPS)
+        thr = torch.from_numpy(thr_np).to(dev)
+        flip = esp.to_packed_tensor(flip_np, dev)
+        dst = torch.empty((rows, c // 64), dtype=esp.PACKED, device=dev)
+        ms, _ = _events_ms(lambda: esp.bn_sign_pack(xi, thr, flip, out=dst), steps, warmup, torch)
+        out.append(_hbm_entry("bn_sign_pack", ms, rows * c * 4 + rows * c // 8 + c * 4 + c // 8,
+                              "int32 [2Mi][128] -> bits (CNN conv2 output, batch 2048)"))
+        del xi, dst
+
+    if want("unroll"):
+        # CNN conv2 input at batch 4096: 64 MiB in -> 576 MiB lowered
+        b, h, c = 4096, 32, 128
+        xin = rand_words((b, h, h, c // 64))
+        low = torch.empty((b * h * h, 9 * c // 64), dtype=esp.PACKED, device=dev)
+        ms, _ = _events_ms(lambda: esp.unroll(xin, c, 3, 3, 1, 1, out=low), steps, warmup, torch)
+        out.append(_hbm_entry("unroll", ms, xin.numel() * 8 + low.numel() * 8,
+                              "packed [4096][32][32][128] 3x3 s1 p1 -> lowered matrix"))
+        del xin, low
+
+    if want("bmaxpool"):
+        b, h, c = 4096, 64, 512
+        xin = rand_words((b, h, h, c // 64))
+        pooled = torch.empty((b, h // 2, h // 2, c // 64), dtype=esp.PACKED, device=dev)
+        ms, _ = _events_ms(lambda: esp.bmaxpool(xin, c, 2, 2, out=pooled), steps, warmup, torch)
+        out.append(_hbm_entry("bmaxpool", ms, xin.numel() * 8 * 1.25, "packed [4096][64][64][512] 2x2 s2 (1 GiB in)"))
+        del xin, pooled
+
+    # small-M bgemm (matrix-vector): config 5's batch-1 product, K = N = 16384 (32 MiB of
+    # weights, cache-resident across repeats) and a 1 GiB weight matrix that is not
+    for name, nrows, kk, label in (
+            ("bgemv", 16384, 16384, "config 5 GEMV M=1, N=K=16384 (32 MiB weights, cache-resident)"),
+            ("bgemv_1g", 524288, 16384, "M=1, N=524288, K=16384 (1 GiB weights)")):
+        if not want(name):
+            continue
+        bw = rand_words((nrows, kk // 64))
+        av = rand_words((1, kk // 64))
         cv = torch.empty((1, nrows), dtype=torch.int32, device=dev)
-        ms, _ = _events_ms(lambda: esp.bgemm(av, bw, kk, out=cv), 20, 3, torch)
+        ms, _ = _events_ms(lambda: esp.bgemm(av, bw, kk, out=cv), steps, warmup, torch)
         e = _hbm_entry("bgemv", ms, nrows * kk // 8 + kk // 8 + nrows * 4, label)
         e["gbops"] = round(2.0 * nrows * kk / (ms * 1e-3) / 1e9, 1)
         out.append(e)
         del bw
+
+    if want("bconv_cfg2"):
+        # config 2: batch 32, 32x32x128 -> 128 filters 3x3 (unroll + bgemm), compute-bound
+        b, h, c, l2 = 32, 32, 128, 128
+        xin = rand_words((b, h, h, c // 64))
+        filt = rand_words((l2, 3, 3, c // 64))
+        ws = torch.empty(esp.bconv_workspace_bytes(b, h, h, c, 3, 3, 1, 1), dtype=torch.uint8, device=dev)
+        pre = torch.empty((b, h, h, l2), dtype=torch.int32, device=dev)
+        ms, _ = _events_ms(lambda: esp.bconv(xin, filt, c, 1, 1, workspace=ws, out=pre), steps, warmup, torch)
+        bop = 2.0 * b * h * h * l2 * 9 * c
+        tb = bop / (ms * 1e-3) / 1e12
+        out.append({"kernel": "bconv (unroll + bgemm)", "workload": "config 2: [32][32][32][128] * 128 x 3x3x128",
+                    "ms": round(ms, 5), "bound": "alu", "achieved": round(tb, 2),
+                    "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s", "frac": round(tb / VALU_PEAK_TBOPS, 4)})
     return out
 
 
-def _networks(torch, esp, nets, synth, dev):
+def _networks(torch, esp, nets, synth, dev, only=None):
     """images/s of the two networks; batch 1 is timed both eagerly and as a replayed HIP graph."""
     res = {"bmlp": {}, "bcnn": {}}
 
@@ -229,12 +285,16 @@ def _networks(torch, esp, nets, synth, dev):
 
     layers = synth.mlp_params()
     for batch in (1, 64, 1024):
+        if only and only != ("bmlp", batch):
+            continue
         net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev)
         x = torch.from_numpy(synth.mlp_input(batch)).to(dev)
         res["bmlp"][str(batch)] = time_net(net, x, batch, 50)
         del net
     layers = synth.cnn_params()
     for batch in (1, 256):
+        if only and only != ("bcnn", batch):
+            continue
         net = nets.BinaryCNN(layers, batch, synth.BN_EPS, device=dev)
         x = torch.from_numpy(synth.cnn_input(batch)).to(dev)
         res["bcnn"][str(batch)] = time_net(net, x, batch, 30)
@@ -251,10 +311,11 @@ def _cpu_baseline(a_pm1, b_pm1, n, sample_rows, np):
     threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
     oracle.set_threads(threads)
     probe = oracle.dense_pm1  # plain triple loop, int8 operands, int32 sums
+    probe(a_pm1[:threads], b_pm1[: n // 8])               # first touch / thread start-up
     t0 = time.perf_counter()
-    probe(a_pm1[:threads], b_pm1[: n // 8])
+    probe(a_pm1[: 4 * threads], b_pm1[: n // 4])
     dt = max(time.perf_counter() - t0, 1e-6)
-    rate = threads * (n // 8) * n / dt                     # MAC/s estimate
+    rate = 4 * threads * (n // 4) * n / dt                 # MAC/s estimate
     rows = sample_rows or int(min(n, max(threads, (15.0 * rate) / (n * n))))
     rows = max(threads, rows - rows % threads)
     t0 = time.perf_counter()

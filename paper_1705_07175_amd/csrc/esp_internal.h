@@ -53,9 +53,12 @@ __device__ __forceinline__ uint32_t fd_div(uint32_t n, const FastDiv f)
     return f.div == 1 ? n : (__umulhi(n, f.mul) >> f.shift);
 }
 
-// Number of blocks for a grid-stride kernel: enough to fill 256 CUs several
-// times over without creating millions of tiny blocks.
-inline unsigned grid_for(int64_t work_items, int per_block, int max_blocks = 256 * 32)
+// Number of blocks for a grid-stride kernel.  Measured on MI355X, streaming kernels reach
+// their best HBM bandwidth when the grid covers the whole array with one item per thread
+// (blocks are dispatched in order, so the blocks in flight sweep memory as one front);
+// a few thousand blocks looping with a large stride lose 20-30 %.  Hence the high cap:
+// the loops in the kernels only matter for arrays beyond it.
+inline unsigned grid_for(int64_t work_items, int per_block, int64_t max_blocks = 1ll << 30)
 {
     int64_t b = ceil_div(work_items, per_block);
     if (b < 1)

@@ -141,6 +141,85 @@ void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ fil
     }
 }
 
+// Fast path for small, compile-time filter shapes at stride 1 (the 3x3x3 first layer of the
+// Sec. 6.3 network): lane = output channel with its KH*KW*C filter weights in registers; a
+// wave owns a strip of PIX consecutive output pixels of one output row.  The wave first
+// copies the strip's input window (KH rows x (PIX+KW-1) pixels x C, zeros outside the image)
+// into its private LDS slice, then every lane reads the whole window back with broadcast
+// 16-byte LDS reads, so the inner loop is KH*KW*C register-to-register fused multiply-adds
+// per output with no address arithmetic.  The 64 lanes store 256 contiguous bytes per pixel.
+// A wave walks all strips of its output row, so the weights are fetched once per row.
+template <int C, int KH, int KW, int PIX>
+__global__ __launch_bounds__(256)
+void conv_f32_lane_channel_kernel(const float *__restrict__ in, const float *__restrict__ filt,
+                                  float *__restrict__ out, int H, int W, int L2, int pad,
+                                  int H2, int W2, int cgroups, int tasks)
+{
+    constexpr int T = KH * KW * C;
+    constexpr int RL = (PIX + KW - 1) * C;          // floats per window row
+    constexpr int RLP = (RL + 3) / 4 * 4;           // padded to whole float4s
+    constexpr int WIN = KH * RLP;
+    __shared__ __align__(16) float win_all[4][WIN];
+
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int task = blockIdx.x * (blockDim.x / kWave) + wave;   // wave-uniform
+    if (task >= tasks)
+        return;
+    // task -> (image row bm = b*H2 + m, channel group); channel group fastest
+    const int cg = task % cgroups;
+    const int bm = task / cgroups;
+    const int m = bm % H2;
+    const int b = bm / H2;
+    const int l2 = cg * kWave + lane;
+    const bool lane_ok = l2 < L2;
+
+    float wgt[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+        wgt[t] = lane_ok ? filt[l2 * T + t] : 0.0f;
+
+    float *win = win_all[wave];
+    const float *img = in + (int64_t)b * H * W * C;
+    float *orow = out + ((int64_t)bm * W2) * L2 + l2;
+    for (int n0 = 0; n0 < W2; n0 += PIX) {
+    // window -> LDS (zero padding applied here)
+    for (int i = lane; i < WIN; i += kWave) {
+        const int r = i / RLP, j = i % RLP;
+        const int y = m - pad + r;
+        const int x = n0 - pad + j / C;
+        float v = 0.0f;
+        if (j < RL && y >= 0 && y < H && x >= 0 && x < W)
+            v = img[(y * W + x) * C + j % C];
+        win[i] = v;
+    }
+    // LDS operations of one wave complete in order: no barrier needed for a private slice
+    float wv[WIN];
+#pragma unroll
+    for (int q = 0; q < WIN / 4; ++q) {
+        const float4 t4 = *reinterpret_cast<const float4 *>(win + 4 * q);
+        wv[4 * q + 0] = t4.x;
+        wv[4 * q + 1] = t4.y;
+        wv[4 * q + 2] = t4.z;
+        wv[4 * q + 3] = t4.w;
+    }
+
+#pragma unroll
+    for (int p = 0; p < PIX; ++p) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int dy = 0; dy < KH; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < KW; ++dx)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    acc = fmaf(wv[dy * RLP + (p + dx) * C + c], wgt[(dy * KW + dx) * C + c], acc);
+        if (lane_ok && n0 + p < W2)
+            orow[(int64_t)(n0 + p) * L2] = acc;
+    }
+    } // strips
+}
+
 } // namespace esp
 
 extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
@@ -191,10 +270,22 @@ extern "C" int esp_conv_f32(const float *in, const float *filt, float *out,
         return ESP_EALIGN;
     const int H2 = (H + 2 * pad - kh) / stride + 1;
     const int W2 = (W + 2 * pad - kw) / stride + 1;
+    if (C == 3 && kh == 3 && kw == 3 && stride == 1 && (int64_t)H * W * C < (1ll << 31) &&
+        (int64_t)L2 * 27 < (1ll << 31)) {
+        constexpr int PIX = 8;
+        const int cgroups = (L2 + kWave - 1) / kWave;
+        const int64_t tasks = (int64_t)B * H2 * cgroups;
+        if (tasks < (1ll << 31)) {
+            hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX>), dim3(grid_for(tasks, 4)),
+                               dim3(256), 0, as_stream(stream), in, filt, out, H, W, L2, pad, H2, W2,
+                               cgroups, (int)tasks);
+            return launch_status();
+        }
+    }
     const int64_t total = (int64_t)B * H2 * W2 * L2;
     const size_t lds = (size_t)kh * kw * C * L2 * sizeof(float);
     const int in_lds = lds <= 48 * 1024;
-    const unsigned grid = grid_for(total, 256 * 8);
+    const unsigned grid = grid_for(total, 256 * 8, 256 * 64);
     hipLaunchKernelGGL(conv_f32_kernel, dim3(grid), dim3(256), in_lds ? lds : 0, as_stream(stream), in,
                        filt, out, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, in_lds);
     return launch_status();
