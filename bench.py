@@ -61,8 +61,8 @@ def _hbm_entry(name, ms, algo_bytes, workload):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--size", type=int, default=8192, help="M=N=K of the headline binary GEMM")
     ap.add_argument("--no-extras", action="store_true", help="skip supporting kernels and networks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
