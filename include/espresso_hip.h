@@ -157,8 +157,6 @@ int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
 /*   dense:  X float [M][K], W float [N][K] (+-1 values), Y float [M][N]      */
 /*   conv :  in float [B][H][W][C], filt float [L2][kh][kw][C] (+-1 values),  */
 /*           out float [B][H2][W2][L2], zero padding                          */
-/*   bn_sign_pack_f32: y as in esp_bn_fold evaluated in double on the GPU,    */
-/*           bit = (y >= 0); gamma/beta/mean/var are DEVICE float [C].        */
 /* ------------------------------------------------------------------------- */
 int esp_dense_f32(const float *X, const float *W, float *Y,
                   int64_t M, int64_t N, int64_t K, esp_stream stream);
@@ -167,9 +165,33 @@ int esp_conv_f32(const float *in, const float *filt, float *out,
                  int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
                  esp_stream stream);
 
-int esp_bn_sign_pack_f32(const float *x, const float *gamma, const float *beta,
-                         const float *mean, const float *var, float eps,
+/* ------------------------------------------------------------------------- */
+/* bn_fold_f32 (HOST function, once per layer at load time): the same fold as */
+/* esp_bn_fold for float pre-activations.  With y(x) as defined there (double,*/
+/* left to right), the outputs satisfy for every finite float x               */
+/*   (y(x) >= 0)  ==  (sgn[c] * x >= thr[c])      sgn[c] is +1 or -1,         */
+/* thr[c] = -inf / +inf encode a bit that is constant 1 / 0.                  */
+/*   gamma, beta, mean, var   HOST float [C]     thr, sgn   HOST float [C]    */
+/*                                                                            */
+/* bn_sign_pack_f32: bit c of row r = (sgn[c] * x[r][c] >= thr[c]); NaN -> 0. */
+/*   x float [rows][C]   thr, sgn DEVICE float [C]   out uint64 [rows][Cw]    */
+/*                                                                            */
+/* conv_f32_bn_sign_pack: esp_conv_f32 followed by esp_bn_sign_pack_f32 in    */
+/* one pass; `bits` uint64 [B][H2][W2][ceil(L2/64)] is always written, `pre`  */
+/* (float [B][H2][W2][L2], the pre-activations) only if not NULL.  For filter */
+/* shapes without a fused kernel `pre` is required as scratch                 */
+/* (ESP_EWORKSPACE if NULL).                                                  */
+/* ------------------------------------------------------------------------- */
+int esp_bn_fold_f32(const float *gamma, const float *beta, const float *mean, const float *var,
+                    float eps, int C, float *thr, float *sgn);
+
+int esp_bn_sign_pack_f32(const float *x, const float *thr, const float *sgn,
                          uint64_t *out, int64_t rows, int C, esp_stream stream);
+
+int esp_conv_f32_bn_sign_pack(const float *in, const float *filt, const float *thr, const float *sgn,
+                              uint64_t *bits, float *pre,
+                              int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                              esp_stream stream);
 
 #ifdef __cplusplus
 }

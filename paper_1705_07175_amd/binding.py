@@ -22,7 +22,8 @@ ESP_OK = 0
 EXPORTS = (
     "esp_strerror", "esp_version", "esp_pack_f32", "esp_bgemm", "esp_unroll",
     "esp_bconv_workspace_bytes", "esp_bconv", "esp_bn_fold", "esp_bn_sign_pack",
-    "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_sign_pack_f32",
+    "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
+    "esp_conv_f32_bn_sign_pack",
 )
 
 _lib = None
@@ -57,7 +58,9 @@ def lib() -> ctypes.CDLL:
         l.esp_bmaxpool.argtypes = [vp, vp] + [i32] * 6 + [vp]
         l.esp_dense_f32.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         l.esp_conv_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
-        l.esp_bn_sign_pack_f32.argtypes = [vp, vp, vp, vp, vp, f32, vp, i64, i32, vp]
+        l.esp_bn_fold_f32.argtypes = [vp, vp, vp, vp, f32, i32, vp, vp]
+        l.esp_bn_sign_pack_f32.argtypes = [vp, vp, vp, vp, i64, i32, vp]
+        l.esp_conv_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 9 + [vp]
         for name in EXPORTS:
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
@@ -238,20 +241,50 @@ def conv_f32(x: torch.Tensor, filt: torch.Tensor, stride: int, pad: int,
     return out
 
 
-def bn_sign_pack_f32(x: torch.Tensor, gamma, beta, mean, var, eps: float,
+def bn_fold_f32(gamma, beta, mean, var, eps: float):
+    """``esp_bn_fold_f32`` (host): float32 numpy parameters -> (thr float32 [C], sgn float32 [C])."""
+    g, b, m, v = (np.ascontiguousarray(t, dtype=np.float32) for t in (gamma, beta, mean, var))
+    C = g.shape[0]
+    thr = np.empty(C, dtype=np.float32)
+    sgn = np.empty(C, dtype=np.float32)
+    _check(lib().esp_bn_fold_f32(g.ctypes.data, b.ctypes.data, m.ctypes.data, v.ctypes.data,
+                                 ctypes.c_float(eps), C, thr.ctypes.data, sgn.ctypes.data), "esp_bn_fold_f32")
+    return thr, sgn
+
+
+def bn_sign_pack_f32(x: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
                      out: torch.Tensor | None = None) -> torch.Tensor:
-    """``esp_bn_sign_pack_f32``: float [..., C] -> batch-norm (double) -> sign -> packed [..., Cw]."""
+    """``esp_bn_sign_pack_f32``: float [..., C] + folded float thresholds -> packed [..., Cw]."""
     px = _dev(x, torch.float32, "x")
     C = x.shape[-1]
     rows = x.numel() // C if C else 0
+    if thr.numel() != C or sgn.numel() != C:
+        raise ValueError("thr/sgn size mismatch")
     if out is None:
         out = torch.empty(x.shape[:-1] + (words(C),), dtype=PACKED, device=x.device)
-    ptrs = [_dev(t, torch.float32, n) for t, n in ((gamma, "gamma"), (beta, "beta"), (mean, "mean"), (var, "var"))]
-    for t in (gamma, beta, mean, var):
-        if t.numel() != C:
-            raise ValueError("batch-norm parameter size mismatch")
-    _check(lib().esp_bn_sign_pack_f32(px, *ptrs, ctypes.c_float(eps), _dev(out, PACKED, "out"), rows, C,
-                                      _stream()), "esp_bn_sign_pack_f32")
+    _check(lib().esp_bn_sign_pack_f32(px, _dev(thr, torch.float32, "thr"), _dev(sgn, torch.float32, "sgn"),
+                                      _dev(out, PACKED, "out"), rows, C, _stream()), "esp_bn_sign_pack_f32")
+    return out
+
+
+def conv_f32_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
+                          stride: int, pad: int, out: torch.Tensor | None = None,
+                          pre: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_conv_f32_bn_sign_pack``: float conv + folded batch-norm + sign + pack in one pass.
+    ``pre`` (float [B][H2][W2][L2]) receives the pre-activations if given."""
+    px, pf = _dev(x, torch.float32, "x"), _dev(filt, torch.float32, "filt")
+    B, H, W, C = x.shape
+    L2, kh, kw, C2 = filt.shape
+    if C != C2 or thr.numel() != L2 or sgn.numel() != L2:
+        raise ValueError("shape mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if out is None:
+        out = torch.empty((B, max(H2, 0), max(W2, 0), words(L2)), dtype=PACKED, device=x.device)
+    ppre = _dev(pre, torch.float32, "pre") if pre is not None else None
+    _check(lib().esp_conv_f32_bn_sign_pack(px, pf, _dev(thr, torch.float32, "thr"),
+                                           _dev(sgn, torch.float32, "sgn"), _dev(out, PACKED, "out"), ppre,
+                                           B, H, W, C, L2, kh, kw, stride, pad, _stream()),
+           "esp_conv_f32_bn_sign_pack")
     return out
 
 

@@ -17,11 +17,11 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libespresso_hip.so")
 
-# (source, extra flags).  pack.hip and host.cpp evaluate the batch-norm expression and must
-# round after every operation, hence no fused multiply-add there.
+# (source, extra flags).  host.cpp evaluates the batch-norm expression and must round after
+# every operation, hence no fused multiply-add there.
 SOURCES = (
     ("bgemm.hip", ()),
-    ("pack.hip", ("-ffp-contract=off",)),
+    ("pack.hip", ()),
     ("conv.hip", ()),
     ("float_layers.hip", ()),
     ("host.cpp", ("-ffp-contract=off",)),

@@ -149,11 +149,15 @@ void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ fil
 // 16-byte LDS reads, so the inner loop is KH*KW*C register-to-register fused multiply-adds
 // per output with no address arithmetic.  The 64 lanes store 256 contiguous bytes per pixel.
 // A wave walks all strips of its output row, so the weights are fetched once per row.
-template <int C, int KH, int KW, int PIX>
+// With FUSE the folded batch-norm threshold + sign is applied in the epilogue: the 64-lane
+// comparison mask of a pixel is its packed word, so only bits leave the kernel (the
+// pre-activations are written as well only if `out` is given).
+template <int C, int KH, int KW, int PIX, bool FUSE>
 __global__ __launch_bounds__(256)
 void conv_f32_lane_channel_kernel(const float *__restrict__ in, const float *__restrict__ filt,
-                                  float *__restrict__ out, int H, int W, int L2, int pad,
-                                  int H2, int W2, int cgroups, int tasks)
+                                  float *__restrict__ out, const float *__restrict__ thr,
+                                  const float *__restrict__ sgn, uint64_t *__restrict__ bits,
+                                  int H, int W, int L2, int pad, int H2, int W2, int cgroups, int tasks)
 {
     constexpr int T = KH * KW * C;
     constexpr int RL = (PIX + KW - 1) * C;          // floats per window row
@@ -179,10 +183,17 @@ void conv_f32_lane_channel_kernel(const float *__restrict__ in, const float *__r
     for (int t = 0; t < T; ++t)
         wgt[t] = lane_ok ? filt[l2 * T + t] : 0.0f;
 
+    float th = 0.0f, sg = 1.0f;
+    if (FUSE && lane_ok) {
+        th = thr[l2];
+        sg = sgn[l2];
+    }
+
     float *win = win_all[wave];
     const float *img = in + (int64_t)b * H * W * C;
     float *orow = out + ((int64_t)bm * W2) * L2 + l2;
     for (int n0 = 0; n0 < W2; n0 += PIX) {
+    uint64_t mine = 0;
     // window -> LDS (zero padding applied here)
     for (int i = lane; i < WIN; i += kWave) {
         const int r = i / RLP, j = i % RLP;
@@ -214,9 +225,16 @@ void conv_f32_lane_channel_kernel(const float *__restrict__ in, const float *__r
 #pragma unroll
                 for (int c = 0; c < C; ++c)
                     acc = fmaf(wv[dy * RLP + (p + dx) * C + c], wgt[(dy * KW + dx) * C + c], acc);
-        if (lane_ok && n0 + p < W2)
+        if ((!FUSE || out) && lane_ok && n0 + p < W2)
             orow[(int64_t)(n0 + p) * L2] = acc;
+        if (FUSE) {
+            const uint64_t word = __ballot(lane_ok && sg * acc >= th);
+            if (lane == p)
+                mine = word;
+        }
     }
+    if (FUSE && lane < PIX && n0 + lane < W2)
+        bits[((int64_t)bm * W2 + n0 + lane) * cgroups + cg] = mine;
     } // strips
 }
 
@@ -253,40 +271,113 @@ extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
     return launch_status();
 }
 
-extern "C" int esp_conv_f32(const float *in, const float *filt, float *out,
-                            int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
-                            esp_stream stream)
+namespace esp {
+
+static int conv_f32_launch(const float *in, const float *filt, float *out, const float *thr,
+                           const float *sgn, uint64_t *bits, int B, int H, int W, int C, int L2,
+                           int kh, int kw, int stride, int pad, hipStream_t stream, bool *done)
 {
-    using namespace esp;
+    // fast path: 3x3x3 filters at stride 1 (the first layer of the Sec. 6.3 network)
+    *done = false;
+    const int H2 = (H + 2 * pad - kh) / stride + 1;
+    const int W2 = (W + 2 * pad - kw) / stride + 1;
+    if (!(C == 3 && kh == 3 && kw == 3 && stride == 1 && (int64_t)H * W * C < (1ll << 31) &&
+          (int64_t)L2 * 27 < (1ll << 31)))
+        return ESP_OK;
+    constexpr int PIX = 8;
+    const int cgroups = (L2 + kWave - 1) / kWave;
+    const int64_t tasks = (int64_t)B * H2 * cgroups;
+    if (tasks >= (1ll << 31))
+        return ESP_OK;
+    *done = true;
+    if (bits)
+        hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX, true>), dim3(grid_for(tasks, 4)),
+                           dim3(256), 0, stream, in, filt, out, thr, sgn, bits, H, W, L2, pad, H2, W2,
+                           cgroups, (int)tasks);
+    else
+        hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX, false>), dim3(grid_for(tasks, 4)),
+                           dim3(256), 0, stream, in, filt, out, thr, sgn, bits, H, W, L2, pad, H2, W2,
+                           cgroups, (int)tasks);
+    return launch_status();
+}
+
+static int conv_f32_args(const float *in, const float *filt, int B, int H, int W, int C, int L2,
+                         int kh, int kw, int stride, int pad)
+{
     if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
         return ESP_EINVAL;
     if (stride < 1 || pad < 0 || (int64_t)H + 2 * (int64_t)pad < kh || (int64_t)W + 2 * (int64_t)pad < kw)
         return ESP_ESHAPE;
     if (B == 0)
         return ESP_OK;
-    if (!in || !filt || !out)
+    if (!in || !filt)
         return ESP_EINVAL;
-    if (!aligned(in, 4) || !aligned(filt, 4) || !aligned(out, 4))
+    if (!aligned(in, 4) || !aligned(filt, 4))
         return ESP_EALIGN;
+    return ESP_OK;
+}
+
+static int conv_f32_generic(const float *in, const float *filt, float *out, int B, int H, int W, int C,
+                            int L2, int kh, int kw, int stride, int pad, hipStream_t stream)
+{
     const int H2 = (H + 2 * pad - kh) / stride + 1;
     const int W2 = (W + 2 * pad - kw) / stride + 1;
-    if (C == 3 && kh == 3 && kw == 3 && stride == 1 && (int64_t)H * W * C < (1ll << 31) &&
-        (int64_t)L2 * 27 < (1ll << 31)) {
-        constexpr int PIX = 8;
-        const int cgroups = (L2 + kWave - 1) / kWave;
-        const int64_t tasks = (int64_t)B * H2 * cgroups;
-        if (tasks < (1ll << 31)) {
-            hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX>), dim3(grid_for(tasks, 4)),
-                               dim3(256), 0, as_stream(stream), in, filt, out, H, W, L2, pad, H2, W2,
-                               cgroups, (int)tasks);
-            return launch_status();
-        }
-    }
     const int64_t total = (int64_t)B * H2 * W2 * L2;
     const size_t lds = (size_t)kh * kw * C * L2 * sizeof(float);
     const int in_lds = lds <= 48 * 1024;
     const unsigned grid = grid_for(total, 256 * 8, 256 * 64);
-    hipLaunchKernelGGL(conv_f32_kernel, dim3(grid), dim3(256), in_lds ? lds : 0, as_stream(stream), in,
-                       filt, out, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, in_lds);
+    hipLaunchKernelGGL(conv_f32_kernel, dim3(grid), dim3(256), in_lds ? lds : 0, stream, in, filt, out, B,
+                       H, W, C, L2, kh, kw, stride, pad, H2, W2, in_lds);
     return launch_status();
+}
+
+} // namespace esp
+
+extern "C" int esp_conv_f32(const float *in, const float *filt, float *out,
+                            int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                            esp_stream stream)
+{
+    using namespace esp;
+    const int st = conv_f32_args(in, filt, B, H, W, C, L2, kh, kw, stride, pad);
+    if (st != ESP_OK || B == 0)
+        return st;
+    if (!out)
+        return ESP_EINVAL;
+    if (!aligned(out, 4))
+        return ESP_EALIGN;
+    bool done;
+    const int fs = conv_f32_launch(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw,
+                                   stride, pad, as_stream(stream), &done);
+    if (done)
+        return fs;
+    return conv_f32_generic(in, filt, out, B, H, W, C, L2, kh, kw, stride, pad, as_stream(stream));
+}
+
+extern "C" int esp_conv_f32_bn_sign_pack(const float *in, const float *filt, const float *thr,
+                                         const float *sgn, uint64_t *bits, float *pre,
+                                         int B, int H, int W, int C, int L2, int kh, int kw, int stride,
+                                         int pad, esp_stream stream)
+{
+    using namespace esp;
+    const int st = conv_f32_args(in, filt, B, H, W, C, L2, kh, kw, stride, pad);
+    if (st != ESP_OK || B == 0)
+        return st;
+    if (!thr || !sgn || !bits)
+        return ESP_EINVAL;
+    if (!aligned(thr, 4) || !aligned(sgn, 4) || !aligned(bits, 8) || (pre && !aligned(pre, 4)))
+        return ESP_EALIGN;
+    bool done;
+    const int fs = conv_f32_launch(in, filt, pre, thr, sgn, bits, B, H, W, C, L2, kh, kw, stride, pad,
+                                   as_stream(stream), &done);
+    if (done)
+        return fs;
+    // other filter shapes: the two-kernel route needs the pre-activation buffer
+    if (!pre)
+        return ESP_EWORKSPACE;
+    const int cs = conv_f32_generic(in, filt, pre, B, H, W, C, L2, kh, kw, stride, pad, as_stream(stream));
+    if (cs != ESP_OK)
+        return cs;
+    const int64_t H2 = (H + 2 * pad - kh) / stride + 1;
+    const int64_t W2 = (W + 2 * pad - kw) / stride + 1;
+    return esp_bn_sign_pack_f32(pre, thr, sgn, bits, (int64_t)B * H2 * W2, L2, stream);
 }

@@ -5,6 +5,7 @@
 // Compiled with -ffp-contract=off: every operation of y(x) rounds to double.
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 #include <limits>
 
 #include "espresso_hip.h"
@@ -16,9 +17,10 @@ constexpr int64_t kRange = 1ll << 30; // thresholds are exact for every integer 
 struct Channel {
     double g, b, m, s;
     // y(x) = gamma * (x - mean) / sqrt(var + eps) + beta, left to right.
-    bool nonneg(int64_t x) const
+    bool nonneg(int64_t x) const { return nonneg(static_cast<double>(x)); }
+    bool nonneg(double x) const
     {
-        const double d = static_cast<double>(x) - m;
+        const double d = x - m;
         const double t = g * d;
         const double q = t / s;
         const double y = q + b;
@@ -44,6 +46,22 @@ int64_t first_change(int64_t lo, int64_t hi, bool first, Pred pred)
             hi = mid;
     }
     return hi;
+}
+
+// Finite floats in increasing order <-> consecutive unsigned keys.
+uint32_t float_key(float f)
+{
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+float key_float(uint32_t k)
+{
+    const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
 }
 
 } // namespace
@@ -112,6 +130,47 @@ extern "C" int esp_bn_fold(const float *gamma, const float *beta, const float *m
         thr[c] = t;
         if (flipped)
             flip[c / 64] |= 1ull << (c % 64);
+    }
+    return ESP_OK;
+}
+
+extern "C" int esp_bn_fold_f32(const float *gamma, const float *beta, const float *mean, const float *var,
+                               float eps, int C, float *thr, float *sgn)
+{
+    if (C <= 0 || !gamma || !beta || !mean || !var || !thr || !sgn)
+        return ESP_EINVAL;
+    const float inf = std::numeric_limits<float>::infinity();
+    const int64_t lo = float_key(-std::numeric_limits<float>::max());
+    const int64_t hi = float_key(std::numeric_limits<float>::max());
+    for (int c = 0; c < C; ++c) {
+        Channel ch;
+        ch.g = static_cast<double>(gamma[c]);
+        ch.b = static_cast<double>(beta[c]);
+        ch.m = static_cast<double>(mean[c]);
+        ch.s = std::sqrt(static_cast<double>(var[c]) + static_cast<double>(eps));
+        auto pred = [&](int64_t k) {
+            return ch.nonneg(static_cast<double>(key_float(static_cast<uint32_t>(k))));
+        };
+        float t = -inf, sg = 1.0f; // default: constant 1 (every finite x >= -inf)
+        if (ch.g > 0.0) {
+            const int64_t k0 = first_change(lo, hi, false, pred);
+            if (k0 > hi)
+                t = inf;            // never non-negative: constant 0
+            else if (k0 > lo)
+                t = key_float(static_cast<uint32_t>(k0));
+        } else if (ch.g < 0.0) {
+            const int64_t k0 = first_change(lo, hi, true, pred); // first x with y(x) < 0
+            if (k0 <= lo)
+                t = inf;            // negative everywhere: constant 0
+            else if (k0 <= hi) {    // y >= 0 iff x <= x* = float(k0 - 1) iff -x >= -x*
+                t = -key_float(static_cast<uint32_t>(k0 - 1));
+                sg = -1.0f;
+            }
+        } else if (!pred(float_key(0.0f))) {
+            t = inf;                // gamma == 0 (or NaN): constant sign of beta
+        }
+        thr[c] = t;
+        sgn[c] = sg;
     }
     return ESP_OK;
 }

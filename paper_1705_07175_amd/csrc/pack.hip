@@ -1,7 +1,7 @@
 // Bit-packing kernels (arXiv 1705.07175): sign + pack of float rows (Eq. 1, Sec. 4.2),
 // batch-norm threshold + sign + re-pack of int32 layer outputs (the bit-packing sign
-// activation of Sec. 6.3 "Bit-packing"), and the float batch-norm + sign + pack that
-// follows the real-valued first layer.
+// activation of Sec. 6.3 "Bit-packing"), and the same on the float outputs of the
+// real-valued first layer (batch-norm folded to a float threshold on the host).
 //
 // All three are one pass over a [rows][C] array that emits one bit per element, so they
 // share one bandwidth-oriented skeleton: a wave owns one 64-channel word column w and
@@ -9,9 +9,6 @@
 // (every load instruction of the wave is one contiguous 256-byte segment, kRows of them
 // in flight), the comparison writes its 64-lane result mask straight into a scalar
 // register pair, which IS the packed word, and lanes 0..kRows-1 store one word each.
-//
-// This file is compiled with -ffp-contract=off: the batch-norm expression must round
-// after every operation, like the definition it is checked against.
 #include "esp_internal.h"
 
 namespace esp {
@@ -39,31 +36,17 @@ struct ThresholdI32 {
     __device__ __forceinline__ uint64_t post(uint64_t word, int w) const { return word ^ flip[w]; }
 };
 
-struct BatchNormF32 {
+struct ThresholdF32 {
     using in_t = float;
-    const float *gamma, *beta, *mean, *var;
-    float eps;
-    struct Lane { double g, b, m, s; };
+    const float *thr;
+    const float *sgn;
+    struct Lane { float t, s; };
     __device__ __forceinline__ Lane lane_state(int c, bool in_range) const
     {
-        Lane l{0.0, -1.0, 0.0, 1.0};
-        if (in_range) {
-            l.g = (double)gamma[c];
-            l.b = (double)beta[c];
-            l.m = (double)mean[c];
-            l.s = __dsqrt_rn(__dadd_rn((double)var[c], (double)eps));
-        }
-        return l;
+        return in_range ? Lane{thr[c], sgn[c]} : Lane{0.0f, 1.0f};
     }
-    __device__ __forceinline__ bool bit(float x, const Lane &l) const
-    {
-        // y = gamma * (x - mean) / sqrt(var + eps) + beta, left to right, every step rounded
-        const double d = __dsub_rn((double)x, l.m);
-        const double t = __dmul_rn(l.g, d);
-        const double q = __ddiv_rn(t, l.s);
-        const double y = __dadd_rn(q, l.b);
-        return y >= 0.0;
-    }
+    // sgn is +1 or -1, so sgn * x is exact; NaN compares false (bit 0)
+    __device__ __forceinline__ bool bit(float x, const Lane &l) const { return l.s * x >= l.t; }
     __device__ __forceinline__ uint64_t post(uint64_t word, int /*w*/) const { return word; }
 };
 
@@ -152,8 +135,7 @@ extern "C" int esp_bn_sign_pack(const int32_t *x, const int32_t *thr, const uint
     return launch_rowbits<ThresholdI32>(x, out, rows, C, ThresholdI32{thr, flip}, as_stream(stream));
 }
 
-extern "C" int esp_bn_sign_pack_f32(const float *x, const float *gamma, const float *beta,
-                                    const float *mean, const float *var, float eps,
+extern "C" int esp_bn_sign_pack_f32(const float *x, const float *thr, const float *sgn,
                                     uint64_t *out, int64_t rows, int C, esp_stream stream)
 {
     using namespace esp;
@@ -161,11 +143,9 @@ extern "C" int esp_bn_sign_pack_f32(const float *x, const float *gamma, const fl
         return ESP_EINVAL;
     if (rows == 0)
         return ESP_OK;
-    if (!x || !gamma || !beta || !mean || !var || !out)
+    if (!x || !thr || !sgn || !out)
         return ESP_EINVAL;
-    if (!aligned(x, 4) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) ||
-        !aligned(var, 4) || !aligned(out, 8))
+    if (!aligned(x, 4) || !aligned(thr, 4) || !aligned(sgn, 4) || !aligned(out, 8))
         return ESP_EALIGN;
-    return launch_rowbits<BatchNormF32>(x, out, rows, C, BatchNormF32{gamma, beta, mean, var, eps},
-                                        as_stream(stream));
+    return launch_rowbits<ThresholdF32>(x, out, rows, C, ThresholdF32{thr, sgn}, as_stream(stream));
 }

@@ -22,15 +22,18 @@ def _dev_f32(a, device):
 
 
 class _FoldedBN:
-    """Batch-norm parameters: raw float (first layer) and folded integer thresholds."""
+    """Batch-norm + sign folded at load time: integer thresholds + flip bits for the binary
+    layers, float thresholds + signs for the real-valued first layer."""
 
-    def __init__(self, bnp, eps, device, fold=True):
-        self.eps = float(eps)
-        self.raw = tuple(_dev_f32(t, device) for t in bnp)
-        if fold:
-            thr, flip = esp.bn_fold(*bnp, self.eps)
+    def __init__(self, bnp, eps, device, integer=True):
+        if integer:
+            thr, flip = esp.bn_fold(*bnp, float(eps))
             self.thr = torch.from_numpy(thr).to(device)
             self.flip = esp.to_packed_tensor(flip, device)
+        else:
+            thr, sgn = esp.bn_fold_f32(*bnp, float(eps))
+            self.thr = torch.from_numpy(thr).to(device)
+            self.sgn = torch.from_numpy(sgn).to(device)
 
 
 def _pack_weights(w_pm1: np.ndarray, device) -> torch.Tensor:
@@ -45,7 +48,7 @@ class BinaryMLP:
         self.batch = batch
         self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
         self.w1 = _dev_f32(layers[0]["w"], device)
-        self.bn = [_FoldedBN(l["bn"], eps, device, fold=(i > 0)) if l["bn"] is not None else None
+        self.bn = [_FoldedBN(l["bn"], eps, device, integer=(i > 0)) if l["bn"] is not None else None
                    for i, l in enumerate(layers)]
         self.wp = [None] + [_pack_weights(l["w"], device) for l in layers[1:]]
         # pre-allocated activations
@@ -57,7 +60,7 @@ class BinaryMLP:
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         esp.dense_f32(x, self.w1, out=self.pre[0])
-        esp.bn_sign_pack_f32(self.pre[0], *self.bn[0].raw, self.bn[0].eps, out=self.act[0])
+        esp.bn_sign_pack_f32(self.pre[0], self.bn[0].thr, self.bn[0].sgn, out=self.act[0])
         for i in range(1, len(self.wp)):
             esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
             if self.bn[i] is not None:
@@ -77,8 +80,10 @@ class BinaryMLP:
 class BinaryCNN:
     """Sec. 6.3 network: float conv, binary 3x3 convs (border = -1), OR max-pools, binary dense."""
 
-    def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda"):
+    def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda",
+                 keep_first_pre: bool = False):
         self.batch = batch
+        self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
         self.steps = []          # one record per layer, in order
         h = hw
         c = layers[0]["w"].shape[3]
@@ -97,7 +102,7 @@ class BinaryCNN:
                 if i == 0:
                     rec["w"] = _dev_f32(l["w"], device)
                     rec["pre"] = torch.empty((batch, h, h, l2), dtype=torch.float32, device=device)
-                    rec["bn"] = _FoldedBN(l["bn"], eps, device, fold=False)
+                    rec["bn"] = _FoldedBN(l["bn"], eps, device, integer=False)
                 else:
                     rec["w"] = _pack_weights(l["w"], device)
                     rec["pre"] = torch.empty((batch, h, h, l2), dtype=torch.int32, device=device)
@@ -130,8 +135,8 @@ class BinaryCNN:
                 cur = esp.bmaxpool(cur, s["c"], 2, 2, out=s["out"])
             elif kind == "conv" and i == 0:
                 if first_act is None:
-                    esp.conv_f32(x, s["w"], 1, 1, out=s["pre"])
-                    esp.bn_sign_pack_f32(s["pre"], *s["bn"].raw, s["bn"].eps, out=s["out"])
+                    esp.conv_f32_bn_sign_pack(x, s["w"], s["bn"].thr, s["bn"].sgn, 1, 1, out=s["out"],
+                                              pre=s["pre"] if self.keep_first_pre else None)
                 else:
                     s["out"].copy_(first_act)
                 cur = s["out"]

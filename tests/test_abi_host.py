@@ -65,7 +65,9 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bn_sign_pack(p, p, p, p, 4, 0, None) == -1
     assert lib.esp_dense_f32(p, None, p, 4, 4, 4, None) == -1
     assert lib.esp_conv_f32(p, p, p, 1, 4, 4, 3, 8, 3, 3, 0, 1, None) == -3
-    assert lib.esp_bn_sign_pack_f32(p, p, p, p, None, 1e-4, p, 4, 64, None) == -1
+    assert lib.esp_bn_sign_pack_f32(p, p, None, p, 4, 64, None) == -1
+    assert lib.esp_bn_fold_f32(p, p, p, None, 1e-4, 4, p, p) == -1
+    assert lib.esp_conv_f32_bn_sign_pack(p, p, p, p, None, None, 1, 4, 4, 3, 8, 3, 3, 1, 1, None) == -1
     assert lib.esp_bn_fold(None, p, p, p, 1e-4, 4, p, p) == -1
 
 
@@ -116,3 +118,33 @@ def test_bn_fold_tail_channels_and_flip_words():
     thr, flip = esp.bn_fold(g, b, m, v, 1e-4)
     assert thr.shape == (70,) and flip.shape == (2,)
     assert int(flip[1]) >> 6 == 0      # bits above channel 69 stay clear
+
+
+def test_bn_fold_f32_matches_oracle_around_every_threshold():
+    # the float fold must reproduce sign(batch-norm(x)) for every float x: check a dense set of
+    # floats around each channel's threshold, plus zeros, extremes and random values
+    rng = np.random.default_rng(9)
+    C = 96
+    g, b, m, v = synth.bn_params(rng, C)
+    g[:4] = [0.0, 0.0, 1e-30, -1e-30]
+    b[:4] = [0.5, -0.5, 1.0, -1.0]
+    g[4:8] = [1.0, -1.0, 2.0, -3.0]
+    b[4:8] = [1e30, 1e30, -1e30, -1e30]          # never / always flips within finite floats
+    thr, sgn = esp.bn_fold_f32(g, b, m, v, synth.BN_EPS)
+    assert set(np.unique(sgn)) <= {-1.0, 1.0}
+    cols = []
+    t = np.where(np.isfinite(thr), sgn * thr, 0.0).astype(np.float32)
+    lo, hi = t.copy(), t.copy()
+    cols.append(t.copy())
+    for _ in range(40):
+        lo = np.nextafter(lo, np.float32(-np.inf))
+        hi = np.nextafter(hi, np.float32(np.inf))
+        cols += [lo.copy(), hi.copy()]
+    fmax = np.finfo(np.float32).max
+    for val in (0.0, -0.0, fmax, -fmax, 1e-45, -1e-45):
+        cols.append(np.full(C, val, dtype=np.float32))
+    cols += list((rng.standard_normal((200, C)) * 50).astype(np.float32))
+    x = np.stack(cols)
+    want = oracle.sign(oracle.bn(x.astype(np.float64), g, b, m, v, synth.BN_EPS)) > 0
+    got = (sgn[None, :] * x) >= thr[None, :]
+    assert np.array_equal(got, want)

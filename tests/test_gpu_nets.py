@@ -98,7 +98,7 @@ def _check_cnn(net, x, layers, rows):
 def test_cnn_forward(batch):
     layers = synth.cnn_params()
     x = synth.cnn_input(batch)
-    net = nets.BinaryCNN(layers, batch, EPS, device=DEV)
+    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
     want = _check_cnn(net, x, layers, np.arange(batch))
@@ -108,7 +108,7 @@ def test_cnn_forward(batch):
 def test_cnn_batch256_sampled_images():
     layers = synth.cnn_params()
     x = synth.cnn_input(256)
-    net = nets.BinaryCNN(layers, 256, EPS, device=DEV)
+    net = nets.BinaryCNN(layers, 256, EPS, device=DEV, keep_first_pre=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     rows = np.array([0, 100, 255])
     want = _check_cnn(net, x, layers, rows)

@@ -279,8 +279,9 @@ def test_conv_f32(B, H, W, C, L2, k, stride, pad):
 
 
 def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
-    # Batch-norm runs in double on the GPU with the oracle's operation order, so on the SAME
-    # float32 pre-activations the sign bits are identical, ties and near-ties included.
+    # Batch-norm + sign is folded on the host to a float threshold per channel that is exact
+    # for every float input, so on the SAME float32 pre-activations the bits equal the
+    # oracle's double-precision batch-norm + sign, ties and near-ties included.
     rng = np.random.default_rng(3)
     rows, C = 300, 200
     bnp = synth.bn_params(rng, C)
@@ -289,6 +290,36 @@ def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
     # plant exact zeros of y: gamma * (x - mean) / s + beta == 0 needs beta = 0, x = mean
     b[:5] = 0.0
     x[:, :5] = m[:5]
-    got = esp.bn_sign_pack_f32(_f32(x), _f32(g), _f32(b), _f32(m), _f32(v), synth.BN_EPS)
+    thr, sgn = esp.bn_fold_f32(g, b, m, v, synth.BN_EPS)
+    # plant values at and next to every threshold (both sides)
+    t = np.where(np.isfinite(thr), sgn * thr, 0.0).astype(np.float32)
+    x[5, :] = t
+    x[6, :] = np.nextafter(t, np.float32(np.inf))
+    x[7, :] = np.nextafter(t, np.float32(-np.inf))
+    x[8, :] = 0.0
+    x[9, :] = -0.0
+    got = esp.bn_sign_pack_f32(_f32(x), _f32(thr), _f32(sgn))
     want = oracle.pack_bits(oracle.bn_sign(x.astype(np.float64), (g, b, m, v), synth.BN_EPS))
     assert np.array_equal(esp.packed_to_numpy(got), want)
+
+
+def test_conv_f32_bn_sign_pack_fused_equals_two_step():
+    rng = np.random.default_rng(4)
+    for (B, H, W, C, L2, k, stride, pad) in [(3, 32, 32, 3, 128, 3, 1, 1), (2, 9, 11, 3, 70, 3, 1, 1),
+                                             (2, 8, 8, 5, 40, 3, 1, 0), (1, 7, 7, 3, 64, 3, 2, 1)]:
+        x = rng.random((B, H, W, C), dtype=np.float32)
+        f = _pm1(rng, (L2, k, k, C))
+        bnp = synth.bn_params(rng, L2)
+        thr, sgn = esp.bn_fold_f32(*bnp, synth.BN_EPS)
+        xd, fd, td, sd = _f32(x), _f32(f), _f32(thr), _f32(sgn)
+        pre = esp.conv_f32(xd, fd, stride, pad)
+        two = esp.bn_sign_pack_f32(pre, td, sd)
+        pre2 = torch.empty_like(pre)
+        fused = esp.conv_f32_bn_sign_pack(xd, fd, td, sd, stride, pad, pre=pre2)
+        assert torch.equal(pre, pre2)
+        assert torch.equal(fused, two)
+        # bits equal the oracle's batch-norm + sign of those same fp32 pre-activations
+        want = oracle.pack_bits(oracle.bn_sign(pre.cpu().numpy().astype(np.float64), bnp, synth.BN_EPS))
+        assert np.array_equal(esp.packed_to_numpy(fused), want)
+        if (C, k, stride) == (3, 3, 1):
+            assert torch.equal(esp.conv_f32_bn_sign_pack(xd, fd, td, sd, stride, pad), two)
