@@ -110,9 +110,15 @@ int esp_unroll(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
 /*   out   int32  [B][H2][W2][L2]    +-1 cross-correlation over kh*kw*C taps, */
 /*                                    border = -1                             */
 /*   workspace  device scratch of at least esp_bconv_workspace_bytes(...)     */
-/*              bytes, 16-byte aligned (holds the lowered matrix).            */
+/*              bytes, 16-byte aligned (holds the lowered matrix).  When C is */
+/*              a multiple of 128 (esp_bconv_needs_workspace(C) == 0) and in, */
+/*              filt are 16-byte aligned, the sliding volumes are gathered    */
+/*              inside the product kernel, no lowered matrix is written and   */
+/*              the workspace is not touched (it may then be NULL).           */
 /* ------------------------------------------------------------------------- */
 size_t esp_bconv_workspace_bytes(int B, int H, int W, int C, int kh, int kw, int stride, int pad);
+
+int esp_bconv_needs_workspace(int C);
 
 int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
               int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
@@ -141,6 +147,28 @@ int esp_bn_fold(const float *gamma, const float *beta, const float *mean, const 
 /* ------------------------------------------------------------------------- */
 int esp_bn_sign_pack(const int32_t *x, const int32_t *thr, const uint64_t *flip,
                      uint64_t *out, int64_t rows, int C, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
+/* Fused layer outputs: the folded threshold of esp_bn_fold applied in the    */
+/* epilogue of the product, so that a binary layer writes the packed sign     */
+/* bits of the next layer directly and its int32 pre-activations never reach  */
+/* memory (Sec. 6.3 "Bit-packing" names this re-packing as the growing cost   */
+/* of convolutional layers).  Results are identical to esp_bgemm / esp_bconv  */
+/* followed by esp_bn_sign_pack.                                              */
+/*   bgemm_bn_sign_pack:  A [M][Kw], B [N][Kw] -> out uint64 [M][ceil(N/64)]  */
+/*   bconv_bn_sign_pack:  in [B][H][W][Cw], filt [L2][kh][kw][Cw]             */
+/*                        -> out uint64 [B][H2][W2][ceil(L2/64)]              */
+/*   thr int32 [N or L2], flip uint64 [ceil(N or L2 / 64)]; workspace as for  */
+/*   esp_bconv.                                                               */
+/* ------------------------------------------------------------------------- */
+int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, const int32_t *thr,
+                           const uint64_t *flip, uint64_t *out,
+                           int64_t M, int64_t N, int64_t K, esp_stream stream);
+
+int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
+                           const uint64_t *flip, uint64_t *out,
+                           int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                           void *workspace, size_t workspace_bytes, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
 /* bmaxpool: max-pooling of +-1 activations on packed words (pooling layer of */

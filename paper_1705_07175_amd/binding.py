@@ -23,7 +23,8 @@ EXPORTS = (
     "esp_strerror", "esp_version", "esp_pack_f32", "esp_bgemm", "esp_unroll",
     "esp_bconv_workspace_bytes", "esp_bconv", "esp_bn_fold", "esp_bn_sign_pack",
     "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
-    "esp_conv_f32_bn_sign_pack",
+    "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
+    "esp_bconv_bn_sign_pack",
 )
 
 _lib = None
@@ -61,6 +62,9 @@ def lib() -> ctypes.CDLL:
         l.esp_bn_fold_f32.argtypes = [vp, vp, vp, vp, f32, i32, vp, vp]
         l.esp_bn_sign_pack_f32.argtypes = [vp, vp, vp, vp, i64, i32, vp]
         l.esp_conv_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 9 + [vp]
+        l.esp_bconv_needs_workspace.argtypes = [i32]
+        l.esp_bgemm_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        l.esp_bconv_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
         for name in EXPORTS:
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
@@ -168,6 +172,50 @@ def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
     _check(lib().esp_bconv(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
                            _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
            "esp_bconv")
+    return out
+
+
+def bconv_needs_workspace(c: int) -> bool:
+    return bool(lib().esp_bconv_needs_workspace(int(c)))
+
+
+def bgemm_bn_sign_pack(a: torch.Tensor, b: torch.Tensor, k: int, thr: torch.Tensor, flip: torch.Tensor,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bgemm_bn_sign_pack``: product + folded threshold + sign -> packed [M][ceil(N/64)]."""
+    pa, pb = _dev(a, PACKED, "a"), _dev(b, PACKED, "b")
+    M, N = a.shape[0], b.shape[0]
+    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != words(k) or b.shape[1] != words(k):
+        raise ValueError("a and b must be [rows][ceil(k/64)]")
+    if thr.numel() != N or flip.numel() != words(N):
+        raise ValueError("thr/flip size mismatch")
+    if out is None:
+        out = torch.empty((M, words(N)), dtype=PACKED, device=a.device)
+    _check(lib().esp_bgemm_bn_sign_pack(pa, pb, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
+                                        _dev(out, PACKED, "out"), M, N, int(k), _stream()),
+           "esp_bgemm_bn_sign_pack")
+    return out
+
+
+def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.Tensor, flip: torch.Tensor,
+                       stride: int, pad: int, workspace: torch.Tensor | None = None,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bconv_bn_sign_pack``: convolution + folded threshold + sign -> packed NHWC bits."""
+    px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
+    B, H, W, Cw = x.shape
+    L2, kh, kw, Cw2 = filt.shape
+    if Cw != words(c) or Cw2 != Cw or thr.numel() != L2 or flip.numel() != words(L2):
+        raise ValueError("shape mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if workspace is None and bconv_needs_workspace(c):
+        need = bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((B, max(H2, 0), max(W2, 0), words(L2)), dtype=PACKED, device=x.device)
+    ws_ptr = _dev(workspace, torch.uint8, "workspace") if workspace is not None else None
+    ws_len = workspace.numel() if workspace is not None else 0
+    _check(lib().esp_bconv_bn_sign_pack(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
+                                        _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
+                                        ws_ptr, ws_len, _stream()), "esp_bconv_bn_sign_pack")
     return out
 
 

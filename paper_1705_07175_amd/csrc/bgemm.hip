@@ -9,6 +9,11 @@
 //    of the words.  The paper's own design (shared-memory tiles + register blocking,
 //    Sec. 5.2 "Efficient Matrix multiplication") is kept; tile shapes, the LDS
 //    layout and the block order are chosen for 64-wide wavefronts and 8 XCDs.
+//    The A operand comes either from a packed matrix or, for convolutions, straight
+//    from the packed NHWC input (the unrolling of Sec. 5.2 / Fig. 3 done by the
+//    loader: the lowered matrix never exists in memory).  The epilogue writes either
+//    the int32 dot products or, with the folded batch-norm threshold, the packed
+//    sign bits of the next layer (the bit-packing sign activation of Sec. 6.3).
 //  * bgemv_kernel       -- small M (matrix-vector, Sec. 6.2 "Optimized kernels"):
 //    bandwidth-bound streaming of B with the few A rows held in LDS.
 #include "esp_internal.h"
@@ -23,11 +28,163 @@ constexpr int kStageDw = 32;  // dwords of K per row per stage
 constexpr int kXcd = 8;       // XCDs (one L2 each); blocks are dealt to them round-robin
 constexpr int kGroupM = 8;    // tile rows walked together so A and B slabs stay in one L2
 
-template <int BM, int BN, int TM, int TN, bool VEC16>
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// 16 bytes of row `p` starting at dword kd of a row that is row_dw dwords long.
+template <bool VEC16>
+__device__ __forceinline__ uint4 load_chunk(const uint32_t *__restrict__ p, int kd, int row_dw)
+{
+    uint4 v = zero4();
+    if (VEC16) {
+        if (kd < row_dw)
+            v = *reinterpret_cast<const uint4 *>(p + kd);
+    } else {
+        if (kd < row_dw) {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(p + kd);
+            v.x = lo.x;
+            v.y = lo.y;
+        }
+        if (kd + 2 < row_dw) {
+            const uint2 hi = *reinterpret_cast<const uint2 *>(p + kd + 2);
+            v.z = hi.x;
+            v.w = hi.y;
+        }
+    }
+    return v;
+}
+
+// ---- A operand: rows of a packed matrix ------------------------------------------
+template <bool VEC16>
+struct MatrixA {
+    const uint32_t *base;
+    int rows;    // M
+    int row_dw;  // dwords per row
+    struct Row { const uint32_t *p; };
+    __device__ __forceinline__ Row row(int r) const
+    {
+        return Row{r < rows ? base + (int64_t)r * row_dw : nullptr};
+    }
+    struct Step {};
+    __device__ __forceinline__ Step step(int /*kd*/) const { return Step{}; }
+    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &, int kd) const
+    {
+        return r.p ? load_chunk<VEC16>(r.p, kd, row_dw) : zero4();
+    }
+};
+
+// ---- A operand: the lowered matrix of a convolution, gathered on the fly ----------
+// Row r = (b*H2 + m)*W2 + n is the sliding volume of output pixel (b, m, n); dword kd of
+// that row is dword kd % cdw of input pixel (m*s - p + dy, n*s - p + dx) with
+// tap = kd / cdw = dy*kw + dx; pixels outside the image read as zero words (= -1).
+// Needs cdw % 4 == 0 (C a multiple of 128) so that a 16-byte chunk never straddles taps.
+struct ConvA {
+    const uint32_t *in;
+    int rows;    // B*H2*W2
+    int row_dw;  // kh*kw*cdw
+    int H, W, cdw, stride, pad;
+    FastDiv d_w2, d_h2, d_cdw, d_kw;
+    struct Row { int64_t img; int y0, x0; };   // img < 0: row beyond M
+    __device__ __forceinline__ Row row(int r) const
+    {
+        if (r >= rows)
+            return Row{-1, 0, 0};
+        const uint32_t bm = fd_div((uint32_t)r, d_w2);
+        const uint32_t n = (uint32_t)r - bm * d_w2.div;
+        const uint32_t b = fd_div(bm, d_h2);
+        const uint32_t m = bm - b * d_h2.div;
+        return Row{(int64_t)b * H * W, (int)(m * stride) - pad, (int)(n * stride) - pad};
+    }
+    struct Step { int dy, dx, c; };
+    __device__ __forceinline__ Step step(int kd) const
+    {
+        const uint32_t tap = fd_div((uint32_t)kd, d_cdw);
+        const uint32_t dy = fd_div(tap, d_kw);
+        return Step{(int)dy, (int)(tap - dy * d_kw.div), (int)((uint32_t)kd - tap * d_cdw.div)};
+    }
+    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &s, int kd) const
+    {
+        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
+        if (r.img < 0 || kd >= row_dw || y < 0 || y >= H || x < 0 || x >= W)
+            return zero4();
+        return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)y * W + x) * cdw + s.c);
+    }
+};
+
+// ---- epilogue: int32 dot products ---------------------------------------------------
+struct StoreDots {
+    int32_t *C;
+    int vec_store;
+    // a lane owns, per row, TN/4 runs of four consecutive columns
+    template <int TN, int TX>
+    __device__ __forceinline__ void row(int r, int N, int K_true, int n0, int tx, const int (&acc)[TN]) const
+    {
+        int32_t *crow = C + (int64_t)r * N;
+#pragma unroll
+        for (int jg = 0; jg < TN / 4; ++jg) {
+            const int col = n0 + jg * 4 * TX + tx * 4;
+            int4 v;
+            v.x = K_true - 2 * acc[jg * 4 + 0];
+            v.y = K_true - 2 * acc[jg * 4 + 1];
+            v.z = K_true - 2 * acc[jg * 4 + 2];
+            v.w = K_true - 2 * acc[jg * 4 + 3];
+            if (vec_store && col + 3 < N) {
+                *reinterpret_cast<int4 *>(crow + col) = v;
+            } else {
+                if (col + 0 < N) crow[col + 0] = v.x;
+                if (col + 1 < N) crow[col + 1] = v.y;
+                if (col + 2 < N) crow[col + 2] = v.z;
+                if (col + 3 < N) crow[col + 3] = v.w;
+            }
+        }
+    }
+};
+
+// OR over the 16 lanes of a DPP row; lane 15 of the row ends up with the total.
+__device__ __forceinline__ uint32_t row_or16(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xf, 0xf, true);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112 /* row_shr:2 */, 0xf, 0xf, true);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114 /* row_shr:4 */, 0xf, 0xf, true);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118 /* row_shr:8 */, 0xf, 0xf, true);
+    return v;
+}
+
+// ---- epilogue: folded batch-norm threshold + sign, packed ---------------------------
+// bit n of row r = (dot >= thr[n]) XOR flipbit(n).  The 16 lanes tx = 0..15 that share a
+// row each hold four consecutive bits of a 64-column word; a DPP OR-reduction over those
+// 16 lanes assembles the word and lane tx = 15 stores it.  Requires TX == 16 and the tile
+// origin n0 to be a multiple of 64.  Must be called by all 64 lanes of a wave.
+struct StoreSignBits {
+    uint64_t *out;          // [M][Nw]
+    const int32_t *thr;     // [N]
+    const uint64_t *flip;   // [Nw]
+    int Nw;
+    template <int TN, int TX>
+    __device__ __forceinline__ void row(int r, bool row_ok, int N, int K_true, int n0, int tx,
+                                        const int (&acc)[TN], const int (&th)[TN]) const
+    {
+        static_assert(TX == 16, "a 64-column word is spread over 16 lanes x 4 columns");
+#pragma unroll
+        for (int jg = 0; jg < TN / 4; ++jg) {
+            const int col = n0 + jg * 64 + tx * 4;
+            uint32_t nib = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                nib |= (uint32_t)((col + c < N) && (K_true - 2 * acc[jg * 4 + c] >= th[jg * 4 + c])) << c;
+            const uint32_t lo = row_or16(tx < 8 ? nib << (4 * tx) : 0u);
+            const uint32_t hi = row_or16(tx >= 8 ? nib << (4 * (tx - 8)) : 0u);
+            const int w = (n0 >> 6) + jg;
+            if (row_ok && tx == 15 && w < Nw)
+                out[(int64_t)r * Nw + w] = (((uint64_t)hi << 32) | lo) ^ flip[w];
+        }
+    }
+};
+
+template <int BM, int BN, int TM, int TN, class ASrc, bool VEC16B, bool BITS>
 __global__ __launch_bounds__((BM / TM) * (BN / TN))
-void bgemm_tile_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B,
-                       int32_t *__restrict__ C, int M, int N, int K_true, int row_dw,
-                       int tiles_m, int tiles_n, int tiles_per_xcd, int vec_store)
+void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const StoreDots dots,
+                       const StoreSignBits bits, int M, int N, int K_true, int row_dw,
+                       int tiles_m, int tiles_n, int tiles_per_xcd)
 {
     constexpr int TX = BN / TN;      // threads along N
     constexpr int TY = BM / TM;      // threads along M
@@ -58,59 +215,44 @@ void bgemm_tile_kernel(const uint32_t *__restrict__ A, const uint32_t *__restric
     const int tx = tid % TX;
     const int ty = tid / TX;
 
+    // loader: chunk idx = tid + i*NT covers (row idx / kKG, k-group idx % kKG); NT is a
+    // multiple of kKG, so a thread always loads the same k-group of its rows
     constexpr int A_CH = BM * kKG / NT;
     constexpr int B_CH = BN * kKG / NT;
+    const int kg_mine = tid % kKG;
+    typename ASrc::Row arow[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+        arow[i] = asrc.row(m0 + (tid + i * NT) / kKG);
+    const uint32_t *brow[B_CH];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+        const int n = n0 + (tid + i * NT) / kKG;
+        brow[i] = n < N ? B + (int64_t)n * row_dw : nullptr;
+    }
     uint4 pa[A_CH], pb[B_CH];
 
-    auto fetch = [&](const uint32_t *__restrict__ base, int row, int rows, int kd) -> uint4 {
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < rows) {
-            const uint32_t *p = base + (int64_t)row * row_dw + kd;
-            if (VEC16) {
-                if (kd < row_dw)
-                    v = *reinterpret_cast<const uint4 *>(p);
-            } else {
-                if (kd < row_dw) {
-                    const uint2 lo = *reinterpret_cast<const uint2 *>(p);
-                    v.x = lo.x;
-                    v.y = lo.y;
-                }
-                if (kd + 2 < row_dw) {
-                    const uint2 hi = *reinterpret_cast<const uint2 *>(p + 2);
-                    v.z = hi.x;
-                    v.w = hi.y;
-                }
-            }
-        }
-        return v;
-    };
-
     auto prefetch = [&](int stage) {
+        const int kd = stage * kStageDw + kg_mine * 4;
+        const typename ASrc::Step st = asrc.step(kd);
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int idx = tid + i * NT;
-            pa[i] = fetch(A, m0 + idx / kKG, M, stage * kStageDw + (idx % kKG) * 4);
-        }
+        for (int i = 0; i < A_CH; ++i)
+            pa[i] = asrc.fetch(arow[i], st, kd);
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int idx = tid + i * NT;
-            pb[i] = fetch(B, n0 + idx / kKG, N, stage * kStageDw + (idx % kKG) * 4);
-        }
+        for (int i = 0; i < B_CH; ++i)
+            pb[i] = brow[i] ? load_chunk<VEC16B>(brow[i], kd, row_dw) : zero4();
     };
 
     auto commit = [&]() {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int idx = tid + i * NT;
-            As[idx % kKG][idx / kKG] = pa[i];
-        }
+        for (int i = 0; i < A_CH; ++i)
+            As[kg_mine][(tid + i * NT) / kKG] = pa[i];
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            const int idx = tid + i * NT;
-            const int nl = idx / kKG;
+            const int nl = (tid + i * NT) / kKG;
             // column nl is register column j of lane tx: nl = (j/4)*(4*TX) + tx*4 + j%4
             const int j = (nl / (4 * TX)) * 4 + nl % 4;
-            Bs[idx % kKG][j * TX + (nl % (4 * TX)) / 4] = pb[i];
+            Bs[kg_mine][j * TX + (nl % (4 * TX)) / 4] = pb[i];
         }
     };
 
@@ -152,36 +294,40 @@ void bgemm_tile_kernel(const uint32_t *__restrict__ A, const uint32_t *__restric
         __syncthreads();
     }
 
-    // Epilogue: dot = K - 2 * mismatches; each lane owns runs of four consecutive columns.
+    // Epilogue: dot = K - 2 * mismatches.
+    if (BITS) {
+        int th[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = m0 + ty + TY * i;
-        if (row >= M)
-            continue;
-        int32_t *crow = C + (int64_t)row * N;
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (j / 4) * 4 * TX + tx * 4 + j % 4;
+            th[j] = col < N ? bits.thr[col] : 0;
+        }
 #pragma unroll
-        for (int jg = 0; jg < TN / 4; ++jg) {
-            const int col = n0 + jg * 4 * TX + tx * 4;
-            int4 v;
-            v.x = K_true - 2 * acc[i][jg * 4 + 0];
-            v.y = K_true - 2 * acc[i][jg * 4 + 1];
-            v.z = K_true - 2 * acc[i][jg * 4 + 2];
-            v.w = K_true - 2 * acc[i][jg * 4 + 3];
-            if (vec_store && col + 3 < N) {
-                *reinterpret_cast<int4 *>(crow + col) = v;
-            } else {
-                if (col + 0 < N) crow[col + 0] = v.x;
-                if (col + 1 < N) crow[col + 1] = v.y;
-                if (col + 2 < N) crow[col + 2] = v.z;
-                if (col + 3 < N) crow[col + 3] = v.w;
-            }
+        for (int i = 0; i < TM; ++i) {
+            const int r = m0 + ty + TY * i;
+            bits.template row<TN, TX>(r, r < M, N, K_true, n0, tx, acc[i], th);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int r = m0 + ty + TY * i;
+            if (r < M)
+                dots.template row<TN, TX>(r, N, K_true, n0, tx, acc[i]);
         }
     }
 }
 
-template <int BM, int BN, int TM, int TN>
-static int launch_tile(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
-                       int64_t K_true, int64_t row_words, hipStream_t stream)
+// What the epilogue of a tiled launch produces.
+struct TileOut {
+    int32_t *C = nullptr;            // int32 dots [M][N]            (BITS == false)
+    uint64_t *bits = nullptr;        // packed signs [M][ceil(N/64)] (BITS == true)
+    const int32_t *thr = nullptr;
+    const uint64_t *flip = nullptr;
+};
+
+template <int BM, int BN, int TM, int TN, class ASrc, bool VEC16B>
+static int launch_tile2(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
+                        int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
     const int tiles_m = (int)ceil_div(M, BM);
     const int tiles_n = (int)ceil_div(N, BN);
@@ -191,19 +337,43 @@ static int launch_tile(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t
     const int per_xcd = (int)ceil_div(total, kXcd);
     const dim3 grid((unsigned)(per_xcd * kXcd));
     const dim3 block((BM / TM) * (BN / TN));
+    const StoreDots dots{o.C, (N % 4 == 0) && aligned(o.C, 16)};
+    const StoreSignBits bits{o.bits, o.thr, o.flip, (int)ceil_div(N, 64)};
+    if (o.bits)
+        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, ASrc, VEC16B, true>), grid, block, 0, stream,
+                           asrc, b, dots, bits, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
+                           per_xcd);
+    else
+        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, ASrc, VEC16B, false>), grid, block, 0, stream,
+                           asrc, b, dots, bits, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
+                           per_xcd);
+    return launch_status();
+}
+
+// Tile shape: 128x128 (8x8 counters per lane) when that still gives every CU two blocks,
+// otherwise 64x64 (4x4 per lane), which keeps small-N / small-M products spread out.
+template <class ASrc, bool VEC16B>
+static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_dw, hipStream_t stream)
+{
+    const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
+    if (big_tiles >= 512)
+        return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    return launch_tile2<64, 64, 4, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+}
+
+static int tile_matrix(const uint64_t *A, const uint64_t *B, const TileOut &o, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_words, hipStream_t stream)
+{
     const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
-    const int vec_store = (N % 4 == 0) && aligned(C, 16);
     const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
+    const int row_dw = (int)(row_words * 2);
     if (vec16)
-        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, true>), grid, block, 0, stream, a, b, C,
-                           (int)M, (int)N, (int)K_true, (int)(row_words * 2), tiles_m, tiles_n,
-                           per_xcd, vec_store);
-    else
-        hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, false>), grid, block, 0, stream, a, b, C,
-                           (int)M, (int)N, (int)K_true, (int)(row_words * 2), tiles_m, tiles_n,
-                           per_xcd, vec_store);
-    return launch_status();
+        return launch_tile<MatrixA<true>, true>(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true,
+                                                row_dw, stream);
+    return launch_tile<MatrixA<false>, false>(MatrixA<false>{a, (int)M, row_dw}, b, o, M, N, K_true,
+                                              row_dw, stream);
 }
 
 // ---------------------------------------------------------------------------------
@@ -358,10 +528,60 @@ int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, in
         return launch_gemv<4>(A, B, C, M, N, K_true, row_words, stream);
     if (M <= 8)
         return launch_gemv<8>(A, B, C, M, N, K_true, row_words, stream);
-    const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
-    if (big_tiles >= 512)
-        return launch_tile<128, 128, 8, 8>(A, B, C, M, N, K_true, row_words, stream);
-    return launch_tile<64, 64, 4, 4>(A, B, C, M, N, K_true, row_words, stream);
+    TileOut o;
+    o.C = C;
+    return tile_matrix(A, B, o, M, N, K_true, row_words, stream);
+}
+
+int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
+                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                      hipStream_t stream)
+{
+    if (M == 0)
+        return ESP_OK;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29))
+        return ESP_ESHAPE;
+    TileOut o;
+    o.bits = out;
+    o.thr = thr;
+    o.flip = flip;
+    return tile_matrix(A, B, o, M, N, K_true, row_words, stream);
+}
+
+bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C)
+{
+    return C % 128 == 0 && aligned(in, 16) && aligned(filt, 16);
+}
+
+int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                          const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
+                          int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream)
+{
+    const int64_t M = (int64_t)B * H2 * W2;
+    const int cdw = 2 * (C / 64);
+    const int64_t row_dw = (int64_t)kh * kw * cdw;
+    if (M >= (1ll << 31) || row_dw >= (1ll << 30) || (int64_t)B * H * W * cdw >= (1ll << 40))
+        return ESP_ESHAPE;
+    ConvA a;
+    a.in = reinterpret_cast<const uint32_t *>(in);
+    a.rows = (int)M;
+    a.row_dw = (int)row_dw;
+    a.H = H;
+    a.W = W;
+    a.cdw = cdw;
+    a.stride = stride;
+    a.pad = pad;
+    a.d_w2 = make_fastdiv((uint32_t)W2);
+    a.d_h2 = make_fastdiv((uint32_t)H2);
+    a.d_cdw = make_fastdiv((uint32_t)cdw);
+    a.d_kw = make_fastdiv((uint32_t)kw);
+    TileOut o;
+    o.C = C_out;
+    o.bits = bits_out;
+    o.thr = thr;
+    o.flip = flip;
+    return launch_tile<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2,
+                                    (int64_t)kh * kw * C, row_dw, stream);
 }
 
 } // namespace esp
@@ -381,4 +601,22 @@ extern "C" int esp_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C,
     if (!aligned(A, 8) || !aligned(B, 8) || !aligned(C, 4))
         return ESP_EALIGN;
     return bgemm_launch(A, B, C, M, N, K, ceil_div(K, 64), as_stream(stream));
+}
+
+extern "C" int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, const int32_t *thr,
+                                      const uint64_t *flip, uint64_t *out,
+                                      int64_t M, int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (K >= kMaxK)
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!A || !B || !thr || !flip || !out)
+        return ESP_EINVAL;
+    if (!aligned(A, 8) || !aligned(B, 8) || !aligned(thr, 4) || !aligned(flip, 8) || !aligned(out, 8))
+        return ESP_EALIGN;
+    return bgemm_bits_launch(A, B, thr, flip, out, M, N, K, ceil_div(K, 64), as_stream(stream));
 }

@@ -170,11 +170,16 @@ extern "C" size_t esp_bconv_workspace_bytes(int B, int H, int W, int C, int kh, 
     return (size_t)((int64_t)B * H2 * W2 * kh * kw * ceil_div(C, 64) * 8);
 }
 
-extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
-                         int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
-                         void *workspace, size_t workspace_bytes, esp_stream stream)
+extern "C" int esp_bconv_needs_workspace(int C) { return C % 128 != 0; }
+
+namespace esp {
+
+// Shared by esp_bconv and esp_bconv_bn_sign_pack: exactly one of out_i32 / out_bits is set.
+static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32, const int32_t *thr,
+                     const uint64_t *flip, uint64_t *out_bits, int B, int H, int W, int C, int L2,
+                     int kh, int kw, int stride, int pad, void *workspace, size_t workspace_bytes,
+                     hipStream_t stream)
 {
-    using namespace esp;
     if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
         return ESP_EINVAL;
     int64_t H2, W2;
@@ -185,22 +190,52 @@ extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
         return ESP_ESHAPE;
     if (B == 0)
         return ESP_OK;
-    if (!in || !filt || !out)
+    if (!in || !filt || (!out_i32 && !out_bits) || (out_bits && (!thr || !flip)))
         return ESP_EINVAL;
-    if (!aligned(in, 8) || !aligned(filt, 8) || !aligned(out, 4))
+    if (!aligned(in, 8) || !aligned(filt, 8) || !aligned(out_i32, 4) || !aligned(out_bits, 8) ||
+        !aligned(thr, 4) || !aligned(flip, 8))
         return ESP_EALIGN;
+    if (bconv_implicit_ok(in, filt, C))
+        return bconv_implicit_launch(in, filt, out_i32, thr, flip, out_bits, B, H, W, C, L2, kh, kw,
+                                     stride, pad, (int)H2, (int)W2, stream);
+    // general channel counts: materialise the lowered matrix, then the plain product
     const size_t need = esp_bconv_workspace_bytes(B, H, W, C, kh, kw, stride, pad);
     if (!workspace || workspace_bytes < need)
         return ESP_EWORKSPACE;
     if (!aligned(workspace, 16))
         return ESP_EALIGN;
     uint64_t *lowered = reinterpret_cast<uint64_t *>(workspace);
-    int st = unroll_launch(in, lowered, B, H, W, C, kh, kw, stride, pad, as_stream(stream));
+    const int st = unroll_launch(in, lowered, B, H, W, C, kh, kw, stride, pad, stream);
     if (st != ESP_OK)
         return st;
     const int64_t row_words = (int64_t)kh * kw * ceil_div(C, 64);
-    return bgemm_launch(lowered, filt, out, (int64_t)B * H2 * W2, L2, K_true, row_words,
-                        as_stream(stream));
+    const int64_t M = (int64_t)B * H2 * W2;
+    if (out_bits)
+        return bgemm_bits_launch(lowered, filt, thr, flip, out_bits, M, L2, K_true, row_words, stream);
+    return bgemm_launch(lowered, filt, out_i32, M, L2, K_true, row_words, stream);
+}
+
+} // namespace esp
+
+extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                         int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                         void *workspace, size_t workspace_bytes, esp_stream stream)
+{
+    if (B > 0 && !out)
+        return ESP_EINVAL;
+    return esp::bconv_any(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw, stride, pad,
+                          workspace, workspace_bytes, esp::as_stream(stream));
+}
+
+extern "C" int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
+                                      const uint64_t *flip, uint64_t *out,
+                                      int B, int H, int W, int C, int L2, int kh, int kw, int stride,
+                                      int pad, void *workspace, size_t workspace_bytes, esp_stream stream)
+{
+    if (B > 0 && (!out || !thr || !flip))
+        return ESP_EINVAL;
+    return esp::bconv_any(in, filt, nullptr, thr, flip, out, B, H, W, C, L2, kh, kw, stride, pad,
+                          workspace, workspace_bytes, esp::as_stream(stream));
 }
 
 extern "C" int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,

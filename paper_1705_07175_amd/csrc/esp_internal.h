@@ -74,4 +74,18 @@ inline unsigned grid_for(int64_t work_items, int per_block, int64_t max_blocks =
 int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
                  int64_t K_true, int64_t row_words, hipStream_t stream);
 
+// Same product with the folded batch-norm threshold + sign applied in the epilogue:
+// out [M][ceil(N/64)] packed bits instead of int32 dots.
+int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
+                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                      hipStream_t stream);
+
+// Convolution without a lowered matrix: the tile loader gathers the sliding volumes from
+// the packed NHWC input.  Usable when C is a multiple of 128 and the buffers are 16-byte
+// aligned.  Exactly one of C_out (int32 [B][H2][W2][L2]) and bits_out (+ thr, flip) is set.
+bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C);
+int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                          const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
+                          int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream);
+
 } // namespace esp

@@ -44,8 +44,9 @@ def _pack_weights(w_pm1: np.ndarray, device) -> torch.Tensor:
 class BinaryMLP:
     """Sec. 6.2 network: float dense, then binary dense layers, BN + sign in between."""
 
-    def __init__(self, layers, batch: int, eps: float, device="cuda"):
+    def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True):
         self.batch = batch
+        self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
         self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
         self.w1 = _dev_f32(layers[0]["w"], device)
         self.bn = [_FoldedBN(l["bn"], eps, device, integer=(i > 0)) if l["bn"] is not None else None
@@ -61,19 +62,25 @@ class BinaryMLP:
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         esp.dense_f32(x, self.w1, out=self.pre[0])
         esp.bn_sign_pack_f32(self.pre[0], self.bn[0].thr, self.bn[0].sgn, out=self.act[0])
-        for i in range(1, len(self.wp)):
-            esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
-            if self.bn[i] is not None:
-                esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
+        self._binary_layers()
         return self.pre[-1]
+
+    def _binary_layers(self):
+        for i in range(1, len(self.wp)):
+            if self.bn[i] is None:
+                esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
+            elif self.fused and self.batch > 8:
+                # threshold + sign + pack in the product's epilogue: no int32 round trip
+                esp.bgemm_bn_sign_pack(self.act[i - 1], self.wp[i], self.sizes[i], self.bn[i].thr,
+                                       self.bn[i].flip, out=self.act[i])
+            else:
+                esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
+                esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
 
     def forward_from_first_act(self, act0: torch.Tensor) -> torch.Tensor:
         """Binary layers only, starting from given packed first-layer activations."""
         self.act[0].copy_(act0)
-        for i in range(1, len(self.wp)):
-            esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
-            if self.bn[i] is not None:
-                esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
+        self._binary_layers()
         return self.pre[-1]
 
 
@@ -81,9 +88,10 @@ class BinaryCNN:
     """Sec. 6.3 network: float conv, binary 3x3 convs (border = -1), OR max-pools, binary dense."""
 
     def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda",
-                 keep_first_pre: bool = False):
+                 keep_first_pre: bool = False, fused: bool = True):
         self.batch = batch
         self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
+        self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
         self.steps = []          # one record per layer, in order
         h = hw
         c = layers[0]["w"].shape[3]
@@ -141,13 +149,19 @@ class BinaryCNN:
                     s["out"].copy_(first_act)
                 cur = s["out"]
             elif kind == "conv":
-                esp.bconv(cur, s["w"], s["c"], 1, 1, workspace=self.workspace, out=s["pre"])
-                cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
+                if self.fused:
+                    cur = esp.bconv_bn_sign_pack(cur, s["w"], s["c"], s["bn"].thr, s["bn"].flip, 1, 1,
+                                                 workspace=self.workspace, out=s["out"])
+                else:
+                    esp.bconv(cur, s["w"], s["c"], 1, 1, workspace=self.workspace, out=s["pre"])
+                    cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
             else:
                 a = cur.reshape(self.batch, -1)   # flatten in storage order: free
-                esp.bgemm(a, s["w"], s["k"], out=s["pre"])
-                if s["bn"] is not None:
-                    cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
+                if s["bn"] is None:
+                    cur = esp.bgemm(a, s["w"], s["k"], out=s["pre"])
+                elif self.fused and self.batch > 8:
+                    cur = esp.bgemm_bn_sign_pack(a, s["w"], s["k"], s["bn"].thr, s["bn"].flip, out=s["out"])
                 else:
-                    cur = s["pre"]
+                    esp.bgemm(a, s["w"], s["k"], out=s["pre"])
+                    cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
         return cur

@@ -49,7 +49,7 @@ def _check_first_layer(pre_gpu, act_gpu_words, rec, bnp, C):
 def test_mlp_forward(batch):
     layers = synth.mlp_params()
     x = synth.mlp_input(batch)
-    net = nets.BinaryMLP(layers, batch, EPS, DEV)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=False)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
 
@@ -87,18 +87,18 @@ def _check_cnn(net, x, layers, rows):
     for i, (s, r) in enumerate(zip(net.steps, ref)):
         if i == 0:
             continue
-        if "pre" in r:
+        if "pre" in r and (not net.fused or s.get("bn") is None):
             assert np.array_equal(s["pre"].cpu().numpy()[rows], r["pre"]), i
         if "out" in s and "act" in r:
             assert np.array_equal(esp.packed_to_numpy(s["out"])[rows], oracle.pack_bits(r["act"])), i
     return ref[-1]["pre"]
 
 
-@pytest.mark.parametrize("batch", [1, 3])
-def test_cnn_forward(batch):
+@pytest.mark.parametrize("batch,fused", [(1, False), (3, False), (1, True), (12, True)])
+def test_cnn_forward(batch, fused):
     layers = synth.cnn_params()
     x = synth.cnn_input(batch)
-    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True)
+    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True, fused=fused)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
     want = _check_cnn(net, x, layers, np.arange(batch))

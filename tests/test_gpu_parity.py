@@ -238,6 +238,63 @@ def test_bn_sign_pack(rows, C, K):
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
+# ------------------------------------------------------------------------------ fused epilogues
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (9, 10, 4096), (64, 4096, 1024), (130, 70, 200), (257, 513, 1152),
+                                   (1000, 128, 1152), (5, 1024, 8192), (1024, 1024, 1024)])
+def test_bgemm_bn_sign_pack(M, N, K):
+    rng = np.random.default_rng(M * 31 + N * 17 + K)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    bnp = synth.bn_params(rng, N)
+    # make thresholds fall inside the populated range of dot products (|dot| ~ sqrt(K))
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    got = esp.bgemm_bn_sign_pack(_packed_dev(a), _packed_dev(b), K, torch.from_numpy(thr).to(DEV),
+                                 esp.to_packed_tensor(flip, DEV))
+    want = oracle.pack_bits(oracle.bn_sign(oracle.dense_pm1(a, b), bnp, synth.BN_EPS))
+    assert got.shape == want.shape
+    assert np.array_equal(esp.packed_to_numpy(got), want)
+
+
+def test_bgemm_bn_sign_pack_large_tiles():
+    M, N, K = 2900, 2950, 640
+    rng = np.random.default_rng(77)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * 25).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    got = esp.bgemm_bn_sign_pack(_packed_dev(a), _packed_dev(b), K, torch.from_numpy(thr).to(DEV),
+                                 esp.to_packed_tensor(flip, DEV))
+    want = oracle.pack_bits(oracle.bn_sign(oracle.dense_pm1(a, b), bnp, synth.BN_EPS))
+    assert np.array_equal(esp.packed_to_numpy(got), want)
+
+
+FUSED_CONV_CASES = CONV_CASES + [
+    (2, 32, 32, 128, 128, 3, 3, 1, 1),     # implicit gather, 64x64 tiles
+    (40, 32, 32, 128, 256, 3, 3, 1, 1),    # implicit gather, 128x128 tiles, several K stages
+    (3, 7, 9, 256, 100, 3, 3, 2, 1),
+    (2, 5, 5, 384, 64, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,L2,kh,kw,stride,pad", FUSED_CONV_CASES)
+def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad):
+    rng = np.random.default_rng(B + 10 * H + 100 * C + kh + 1000 * L2 + 5)
+    x = _pm1(rng, (B, H, W, C))
+    f = _pm1(rng, (L2, kh, kw, C))
+    bnp = synth.bn_params(rng, L2)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(kh * kw * C)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    xp, fp = _packed_dev(x), _packed_dev(f)
+    got = esp.bconv_bn_sign_pack(xp, fp, C, torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV),
+                                 stride, pad)
+    pre = oracle.conv_pm1(x, f, stride, pad, -1)
+    want = oracle.pack_bits(oracle.bn_sign(pre, bnp, synth.BN_EPS))
+    assert got.shape == want.shape
+    assert np.array_equal(esp.packed_to_numpy(got), want)
+    # the int32 route through the same loader
+    assert np.array_equal(esp.bconv(xp, fp, C, stride, pad).cpu().numpy(), pre)
+
+
 # ------------------------------------------------------------------------------ bmaxpool
 @pytest.mark.parametrize("B,H,W,C,win,stride", [(1, 2, 2, 64, 2, 2), (2, 8, 8, 128, 2, 2), (3, 7, 9, 192, 2, 2),
                                                 (2, 6, 6, 100, 3, 1), (4, 32, 32, 128, 2, 2),
