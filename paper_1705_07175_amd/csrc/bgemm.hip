@@ -139,44 +139,112 @@ struct StoreDots {
     }
 };
 
-// OR over the 16 lanes of a DPP row; lane 15 of the row ends up with the total.
-__device__ __forceinline__ uint32_t row_or16(uint32_t v)
+// Value of `v` held by lane (lane ^ S) of the same 16-lane row.
+template <int S>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v)
 {
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xf, 0xf, true);
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112 /* row_shr:2 */, 0xf, 0xf, true);
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114 /* row_shr:4 */, 0xf, 0xf, true);
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118 /* row_shr:8 */, 0xf, 0xf, true);
-    return v;
+    if (S == 1)
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, true);
+    if (S == 2)
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E /* quad_perm [2,3,0,1] */, 0xf, 0xf, true);
+    if (S == 4)
+        return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x101F /* lane ^ 4 */);
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128 /* row_ror:8 == lane ^ 8 */, 0xf, 0xf, true);
+}
+
+// One butterfly step of a 16 x 16 nibble transpose across the 16 lanes of a row, on a
+// register holding 8 nibbles: lanes whose index has bit S clear keep the nibbles at
+// positions with bit S clear and receive, into the other positions, the partner's kept
+// nibbles moved up by S positions; lanes with bit S set do the mirror image.
+template <int S>
+__device__ __forceinline__ uint32_t nibble_swap(uint32_t own, bool lane_bit)
+{
+    constexpr uint32_t kHigh = S == 1 ? 0xF0F0F0F0u : (S == 2 ? 0xFF00FF00u : 0xFFFF0000u);
+    const uint32_t p = lane_xor<S>(own);
+    const uint32_t moved = __builtin_amdgcn_alignbit(p, p, lane_bit ? 4 * S : 32 - 4 * S);
+    const uint32_t keep = lane_bit ? kHigh : ~kHigh;
+    return (keep & own) | (~keep & moved);
 }
 
 // ---- epilogue: folded batch-norm threshold + sign, packed ---------------------------
-// bit n of row r = (dot >= thr[n]) XOR flipbit(n).  The 16 lanes tx = 0..15 that share a
-// row each hold four consecutive bits of a 64-column word; a DPP OR-reduction over those
-// 16 lanes assembles the word and lane tx = 15 stores it.  Requires TX == 16 and the tile
-// origin n0 to be a multiple of 64.  Must be called by all 64 lanes of a wave.
+// bit n of row r = (dot >= thr[n]) XOR flipbit(n).  The 16 lanes tx = 0..15 that share the
+// rows ty + TY*i each hold, per row and 64-column word, four consecutive bits (a nibble).
+// Instead of reducing every word over the 16 lanes, the nibbles are transposed across the
+// lanes (4 butterfly steps on two registers), after which lane tx holds one complete word.
+// Requires TX == 16 and a tile origin n0 that is a multiple of 64; all 64 lanes must call.
 struct StoreSignBits {
     uint64_t *out;          // [M][Nw]
     const int32_t *thr;     // [N]
     const uint64_t *flip;   // [Nw]
     int Nw;
-    template <int TN, int TX>
-    __device__ __forceinline__ void row(int r, bool row_ok, int N, int K_true, int n0, int tx,
-                                        const int (&acc)[TN], const int (&th)[TN]) const
+
+    // mismatch-count threshold: dot = K - 2a >= thr  <=>  a <= floor((K - thr) / 2)
+    __device__ __forceinline__ int mismatch_limit(int col, int N, int K_true) const
     {
-        static_assert(TX == 16, "a 64-column word is spread over 16 lanes x 4 columns");
+        if (col >= N)
+            return -1;                                    // tail bits stay 0
+        const int t = min(max(thr[col], -K_true), K_true + 1);
+        return (K_true - t) >> 1;
+    }
+
+    __device__ __forceinline__ void put(int r, int M, int w, uint32_t lo, uint32_t hi) const
+    {
+        if (r < M && w < Nw)
+            out[(int64_t)r * Nw + w] = (((uint64_t)hi << 32) | lo) ^ flip[w];
+    }
+
+    // 8 x 8 counters per lane: slots q = jg*8 + i, lo register = word jg 0, hi = word jg 1
+    template <int TY>
+    __device__ __forceinline__ void tile(const int (&acc)[8][8], const int (&lim)[8], int m0, int n0,
+                                         int M, int tx, int ty) const
+    {
+        uint32_t lo = 0, hi = 0;
 #pragma unroll
-        for (int jg = 0; jg < TN / 4; ++jg) {
-            const int col = n0 + jg * 64 + tx * 4;
-            uint32_t nib = 0;
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                lo |= acc[i][c] <= lim[c] ? 1u << (4 * i + c) : 0u;
+                hi |= acc[i][4 + c] <= lim[4 + c] ? 1u << (4 * i + c) : 0u;
+            }
+        lo = nibble_swap<1>(lo, tx & 1);
+        hi = nibble_swap<1>(hi, tx & 1);
+        lo = nibble_swap<2>(lo, tx & 2);
+        hi = nibble_swap<2>(hi, tx & 2);
+        lo = nibble_swap<4>(lo, tx & 4);
+        hi = nibble_swap<4>(hi, tx & 4);
+        // step 8 moves whole registers: lanes 0-7 take the partner's lo as their hi, lanes
+        // 8-15 take the partner's hi as their lo
+        const bool up = tx & 8;
+        const uint32_t got = lane_xor<8>(up ? lo : hi);
+        lo = up ? got : lo;
+        hi = up ? hi : got;
+        // lane tx now holds the word of slot q = tx: row ty + TY*(tx % 8), word tx / 8
+        put(m0 + ty + TY * (tx & 7), M, (n0 >> 6) + (tx >> 3), lo, hi);
+    }
+
+    // 4 x 4 counters per lane: one word per row i = 0..3
+    template <int TY>
+    __device__ __forceinline__ void tile(const int (&acc)[4][4], const int (&lim)[4], int m0, int n0,
+                                         int M, int tx, int ty) const
+    {
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                nib |= (uint32_t)((col + c < N) && (K_true - 2 * acc[jg * 4 + c] >= th[jg * 4 + c])) << c;
-            const uint32_t lo = row_or16(tx < 8 ? nib << (4 * tx) : 0u);
-            const uint32_t hi = row_or16(tx >= 8 ? nib << (4 * (tx - 8)) : 0u);
-            const int w = (n0 >> 6) + jg;
-            if (row_ok && tx == 15 && w < Nw)
-                out[(int64_t)r * Nw + w] = (((uint64_t)hi << 32) | lo) ^ flip[w];
-        }
+                x |= acc[i][c] <= lim[c] ? 0x10001u << (4 * i + c) : 0u;   // kept 16-bit periodic
+        x = nibble_swap<1>(x, tx & 1);
+        x = nibble_swap<2>(x, tx & 2);
+        // the quad tx/4 now holds, in lane tx, its 16 bits of the word of row i = tx % 4
+        const uint32_t piece = (x & 0xFFFFu) << (16 * ((tx >> 2) & 1));
+        uint32_t lo = (tx & 8) ? 0u : piece;
+        uint32_t hi = (tx & 8) ? piece : 0u;
+        lo |= lane_xor<4>(lo);
+        hi |= lane_xor<4>(hi);
+        lo |= lane_xor<8>(lo);
+        hi |= lane_xor<8>(hi);
+        if (tx < 4)
+            put(m0 + ty + TY * tx, M, n0 >> 6, lo, hi);
     }
 };
 
@@ -295,18 +363,13 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
     }
 
     // Epilogue: dot = K - 2 * mismatches.
-    if (BITS) {
-        int th[TN];
+    if constexpr (BITS) {
+        static_assert(TX == 16, "a 64-column word is spread over 16 lanes x 4 columns");
+        int lim[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (j / 4) * 4 * TX + tx * 4 + j % 4;
-            th[j] = col < N ? bits.thr[col] : 0;
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int r = m0 + ty + TY * i;
-            bits.template row<TN, TX>(r, r < M, N, K_true, n0, tx, acc[i], th);
-        }
+        for (int j = 0; j < TN; ++j)
+            lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+        bits.template tile<TY>(acc, lim, m0, n0, M, tx, ty);
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
