@@ -171,6 +171,26 @@ int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, const int32
                            void *workspace, size_t workspace_bytes, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
+/* Zero-padding correction (Sec. 5.2 "Zero-padding for convolutions"): the    */
+/* binary convolution above treats the border as -1; a zero-padded ("same")   */
+/* convolution is obtained by adding a correction matrix that depends only on */
+/* the weights.                                                               */
+/*   pad_correction (once per layer, at load time):                           */
+/*     corr int32 [H2][W2][L2] = convolution of the weights with a tensor     */
+/*     that is 0 inside the H x W image and +1 in the padding ring; it is     */
+/*     non-zero only where a sliding volume leaves the image.                 */
+/*   add_pad_correction: x[b][m][n][:] += corr[m][n][:] for every image b, IN */
+/*     PLACE on the int32 result of esp_bconv ([B][H2][W2][L2]); only the     */
+/*     border pixels are touched.  After it, x equals the convolution with    */
+/*     zero padding.  The geometry arguments must be those of the bconv call. */
+/* ------------------------------------------------------------------------- */
+int esp_pad_correction(const uint64_t *filt, int32_t *corr, int H, int W, int C, int L2,
+                       int kh, int kw, int stride, int pad, esp_stream stream);
+
+int esp_add_pad_correction(int32_t *x, const int32_t *corr, int B, int H, int W, int L2,
+                           int kh, int kw, int stride, int pad, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
 /* bmaxpool: max-pooling of +-1 activations on packed words (pooling layer of */
 /* Sec. 5.2): the maximum of +-1 values is the bitwise OR of their bits.      */
 /*   in  uint64 [B][H][W][Cw]   out uint64 [B][H2][W2][Cw]                    */

@@ -49,9 +49,12 @@ def mlp_forward(x: np.ndarray, layers, eps: float, first_act: np.ndarray | None 
     return trace
 
 
-def cnn_forward(x: np.ndarray, layers, eps: float, first_act: np.ndarray | None = None):
+def cnn_forward(x: np.ndarray, layers, eps: float, first_act: np.ndarray | None = None,
+                pad_value: int = -1):
     """Sec. 6.3 network.  ``x`` float32 NHWC [B][32][32][3]; ``layers`` as from the generator:
-    {"kind": "conv"|"dense"|"pool", "w": ..., "bn": ...}."""
+    {"kind": "conv"|"dense"|"pool", "w": ..., "bn": ...}.  ``pad_value`` is the border value of
+    the binary convolutions: -1 (the uncorrected kernel of Sec. 5.2 "Zero-padding for
+    convolutions") or 0 (true zero padding, what the correction matrix restores)."""
     trace = []
     act = None
     for i, layer in enumerate(layers):
@@ -64,7 +67,7 @@ def cnn_forward(x: np.ndarray, layers, eps: float, first_act: np.ndarray | None 
             if i == 0:
                 pre = conv_f64(x, layer["w"], stride=1, pad=1)
             else:
-                pre = conv_pm1(act, layer["w"], stride=1, pad=1, pad_value=-1)
+                pre = conv_pm1(act, layer["w"], stride=1, pad=1, pad_value=pad_value)
         else:
             if act.ndim == 4:
                 # Flatten [B][H][W][C] in storage order (Sec. 5.1: element (m,n,l) at (m*N+n)*L+l).

@@ -24,7 +24,7 @@ EXPORTS = (
     "esp_bconv_workspace_bytes", "esp_bconv", "esp_bn_fold", "esp_bn_sign_pack",
     "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
-    "esp_bconv_bn_sign_pack",
+    "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
 )
 
 _lib = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_needs_workspace.argtypes = [i32]
         l.esp_bgemm_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_bconv_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
+        l.esp_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
+        l.esp_add_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
         for name in EXPORTS:
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
@@ -217,6 +219,32 @@ def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.T
                                         _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
                                         ws_ptr, ws_len, _stream()), "esp_bconv_bn_sign_pack")
     return out
+
+
+def pad_correction(filt: torch.Tensor, c: int, h: int, w: int, stride: int, pad: int,
+                   out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_pad_correction``: packed filters [L2][kh][kw][Cw] -> int32 correction [H2][W2][L2]."""
+    pf = _dev(filt, PACKED, "filt")
+    L2, kh, kw, Cw = filt.shape
+    if Cw != words(c):
+        raise ValueError("channel words mismatch")
+    H2, W2 = conv_out(h, kh, stride, pad), conv_out(w, kw, stride, pad)
+    if out is None:
+        out = torch.empty((max(H2, 0), max(W2, 0), L2), dtype=torch.int32, device=filt.device)
+    _check(lib().esp_pad_correction(pf, _dev(out, torch.int32, "out"), h, w, int(c), L2, kh, kw, stride, pad,
+                                    _stream()), "esp_pad_correction")
+    return out
+
+
+def add_pad_correction(x: torch.Tensor, corr: torch.Tensor, h: int, w: int, kh: int, kw: int,
+                       stride: int, pad: int) -> torch.Tensor:
+    """``esp_add_pad_correction``: x int32 [B][H2][W2][L2] += corr [H2][W2][L2], in place."""
+    B, H2, W2, L2 = x.shape
+    if tuple(corr.shape) != (H2, W2, L2):
+        raise ValueError("correction shape mismatch")
+    _check(lib().esp_add_pad_correction(_dev(x, torch.int32, "x"), _dev(corr, torch.int32, "corr"), B, h, w,
+                                        L2, kh, kw, stride, pad, _stream()), "esp_add_pad_correction")
+    return x
 
 
 def bn_fold(gamma, beta, mean, var, eps: float):

@@ -238,6 +238,171 @@ extern "C" int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, 
                           workspace, workspace_bytes, esp::as_stream(stream));
 }
 
+namespace esp {
+
+// Correction matrix of Sec. 5.2 "Zero-padding for convolutions": the convolution of the
+// layer's weights with a tensor that is 0 inside the image and +1 in the padding ring.
+// corr[m][n][l2] = sum over the taps of output pixel (m, n) that fall outside the image of
+// sum_c F[l2][dy][dx][c] = 2 * popcount(filter words of that tap) - C.
+__global__ __launch_bounds__(256)
+void pad_correction_kernel(const uint64_t *__restrict__ filt, int32_t *__restrict__ corr, int H, int W,
+                           int C, int Cw, int L2, int kh, int kw, int stride, int pad, int H2, int W2)
+{
+    const int64_t total = (int64_t)H2 * W2 * L2;
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total)
+        return;
+    const int l2 = (int)(o % L2);
+    const int n = (int)((o / L2) % W2);
+    const int m = (int)(o / ((int64_t)L2 * W2));
+    int acc = 0;
+    for (int dy = 0; dy < kh; ++dy)
+        for (int dx = 0; dx < kw; ++dx) {
+            const int y = m * stride + dy - pad, x = n * stride + dx - pad;
+            if (y >= 0 && y < H && x >= 0 && x < W)
+                continue;
+            const uint64_t *f = filt + (((int64_t)l2 * kh + dy) * kw + dx) * Cw;
+            int ones = 0;
+            for (int w = 0; w < Cw; ++w)
+                ones += __popcll(f[w]);
+            acc += 2 * ones - C;
+        }
+    corr[o] = acc;
+}
+
+// Output pixels whose sliding volume leaves the image: rows [0, mt) and [mb, H2) entirely,
+// and columns [0, nl) and [nr, W2) of the rows in between.
+struct BorderMap {
+    int W2, mt, mb, nl, nr, side, top, mid, count;
+};
+
+static BorderMap make_border(int H, int W, int kh, int kw, int stride, int pad, int H2, int W2)
+{
+    auto first_rows = [&](int n2) { int t = (pad + stride - 1) / stride; return t < n2 ? t : n2; };
+    auto last_start = [&](int size, int k, int n2, int lo) {
+        // first index whose window ends beyond the image
+        int64_t t = ((int64_t)size - k + pad) / stride + 1;
+        if ((int64_t)size - k + pad < 0)
+            t = 0;
+        if (t < lo)
+            t = lo;
+        return (int)(t < n2 ? t : n2);
+    };
+    BorderMap b;
+    b.W2 = W2;
+    b.mt = first_rows(H2);
+    b.mb = last_start(H, kh, H2, b.mt);
+    b.nl = first_rows(W2);
+    b.nr = last_start(W, kw, W2, b.nl);
+    b.side = b.nl + (W2 - b.nr);
+    b.top = b.mt * W2;
+    b.mid = (b.mb - b.mt) * b.side;
+    b.count = b.top + b.mid + (H2 - b.mb) * W2;
+    return b;
+}
+
+// x[b][pixel][:] += corr[pixel][:] for the border pixels only (the correction is zero
+// elsewhere); VEC int32 per thread.
+template <int VEC>
+__global__ __launch_bounds__(256)
+void add_correction_kernel(int32_t *__restrict__ x, const int32_t *__restrict__ corr, int B,
+                           int pixels, int L2, BorderMap bm)
+{
+    const int lv = L2 / VEC;
+    const int64_t total = (int64_t)B * bm.count * lv;
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total)
+        return;
+    const int cv = (int)(o % lv);
+    const int idx = (int)((o / lv) % bm.count);
+    const int b = (int)(o / ((int64_t)lv * bm.count));
+    int m, n;
+    if (idx < bm.top) {
+        m = idx / bm.W2;
+        n = idx - m * bm.W2;
+    } else if (idx < bm.top + bm.mid) {
+        const int r = idx - bm.top;
+        const int q = r / bm.side, j = r - q * bm.side;
+        m = bm.mt + q;
+        n = j < bm.nl ? j : bm.nr + (j - bm.nl);
+    } else {
+        const int r = idx - bm.top - bm.mid;
+        const int q = r / bm.W2;
+        m = bm.mb + q;
+        n = r - q * bm.W2;
+    }
+    const int64_t pix = (int64_t)m * bm.W2 + n;
+    int32_t *px = x + ((int64_t)b * pixels + pix) * L2 + cv * VEC;
+    const int32_t *pc = corr + pix * L2 + cv * VEC;
+    if (VEC == 4) {
+        int4 v = *reinterpret_cast<int4 *>(px);
+        const int4 c = *reinterpret_cast<const int4 *>(pc);
+        v.x += c.x;
+        v.y += c.y;
+        v.z += c.z;
+        v.w += c.w;
+        *reinterpret_cast<int4 *>(px) = v;
+    } else {
+        *px += *pc;
+    }
+}
+
+} // namespace esp
+
+extern "C" int esp_pad_correction(const uint64_t *filt, int32_t *corr, int H, int W, int C, int L2,
+                                  int kh, int kw, int stride, int pad, esp_stream stream)
+{
+    using namespace esp;
+    if (H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
+        return ESP_EINVAL;
+    int64_t H2, W2;
+    if (!conv_shape_ok(1, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return ESP_ESHAPE;
+    if (!filt || !corr)
+        return ESP_EINVAL;
+    if (!aligned(filt, 8) || !aligned(corr, 4))
+        return ESP_EALIGN;
+    const int64_t total = H2 * W2 * L2;
+    if (total >= (1ll << 38))
+        return ESP_ESHAPE;
+    hipLaunchKernelGGL(pad_correction_kernel, dim3(grid_for(total, 256)), dim3(256), 0, as_stream(stream),
+                       filt, corr, H, W, C, (int)ceil_div(C, 64), L2, kh, kw, stride, pad, (int)H2, (int)W2);
+    return launch_status();
+}
+
+extern "C" int esp_add_pad_correction(int32_t *x, const int32_t *corr, int B, int H, int W, int L2,
+                                      int kh, int kw, int stride, int pad, esp_stream stream)
+{
+    using namespace esp;
+    if (B < 0 || H <= 0 || W <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
+        return ESP_EINVAL;
+    int64_t H2, W2;
+    if (!conv_shape_ok(B, H, W, 1, kh, kw, stride, pad, &H2, &W2))
+        return ESP_ESHAPE;
+    if (B == 0)
+        return ESP_OK;
+    if (!x || !corr)
+        return ESP_EINVAL;
+    if (!aligned(x, 4) || !aligned(corr, 4))
+        return ESP_EALIGN;
+    if (H2 * W2 >= (1ll << 31))
+        return ESP_ESHAPE;
+    const BorderMap bm = make_border(H, W, kh, kw, stride, pad, (int)H2, (int)W2);
+    if (bm.count == 0)
+        return ESP_OK;
+    const bool vec4 = (L2 % 4 == 0) && aligned(x, 16) && aligned(corr, 16);
+    const int64_t total = (int64_t)B * bm.count * (vec4 ? L2 / 4 : L2);
+    if (total >= (1ll << 38))
+        return ESP_ESHAPE;
+    if (vec4)
+        hipLaunchKernelGGL((add_correction_kernel<4>), dim3(grid_for(total, 256)), dim3(256), 0,
+                           as_stream(stream), x, corr, B, (int)(H2 * W2), L2, bm);
+    else
+        hipLaunchKernelGGL((add_correction_kernel<1>), dim3(grid_for(total, 256)), dim3(256), 0,
+                           as_stream(stream), x, corr, B, (int)(H2 * W2), L2, bm);
+    return launch_status();
+}
+
 extern "C" int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
                             int win, int stride, esp_stream stream)
 {

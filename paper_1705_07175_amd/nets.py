@@ -88,8 +88,13 @@ class BinaryCNN:
     """Sec. 6.3 network: float conv, binary 3x3 convs (border = -1), OR max-pools, binary dense."""
 
     def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda",
-                 keep_first_pre: bool = False, fused: bool = True):
+                 keep_first_pre: bool = False, fused: bool = True, zero_pad: bool = False):
         self.batch = batch
+        # zero_pad: add the load-time correction matrix (Sec. 5.2 "Zero-padding for
+        # convolutions") after every binary convolution, i.e. true zero padding
+        self.zero_pad = zero_pad
+        if zero_pad:
+            fused = False
         self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
         self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
         self.steps = []          # one record per layer, in order
@@ -116,6 +121,8 @@ class BinaryCNN:
                     rec["pre"] = torch.empty((batch, h, h, l2), dtype=torch.int32, device=device)
                     rec["bn"] = _FoldedBN(l["bn"], eps, device)
                     ws_bytes = max(ws_bytes, esp.bconv_workspace_bytes(batch, h, h, c, 3, 3, 1, 1))
+                    if zero_pad:
+                        rec["corr"] = esp.pad_correction(rec["w"], c, h, h, 1, 1)
                 rec["out"] = torch.empty((batch, h, h, esp.words(l2)), dtype=esp.PACKED, device=device)
                 c = l2
             else:
@@ -154,6 +161,8 @@ class BinaryCNN:
                                                  workspace=self.workspace, out=s["out"])
                 else:
                     esp.bconv(cur, s["w"], s["c"], 1, 1, workspace=self.workspace, out=s["pre"])
+                    if self.zero_pad:
+                        esp.add_pad_correction(s["pre"], s["corr"], s["h"], s["h"], 3, 3, 1, 1)
                     cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])
             else:
                 a = cur.reshape(self.batch, -1)   # flatten in storage order: free

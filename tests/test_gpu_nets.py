@@ -78,12 +78,12 @@ def test_mlp_batch1024_sampled_rows():
     assert np.array_equal(scores[rows], ref[3]["pre"])
 
 
-def _check_cnn(net, x, layers, rows):
+def _check_cnn(net, x, layers, rows, pad_value=-1):
     first = net.steps[0]
     ref = onets.cnn_forward(x[rows], layers, EPS)
     act0 = _check_first_layer(first["pre"].cpu().numpy()[rows], esp.packed_to_numpy(first["out"])[rows],
                               ref[0], layers[0]["bn"], 128)
-    ref = onets.cnn_forward(x[rows], layers, EPS, first_act=act0)
+    ref = onets.cnn_forward(x[rows], layers, EPS, first_act=act0, pad_value=pad_value)
     for i, (s, r) in enumerate(zip(net.steps, ref)):
         if i == 0:
             continue
@@ -102,6 +102,16 @@ def test_cnn_forward(batch, fused):
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
     want = _check_cnn(net, x, layers, np.arange(batch))
+    assert np.array_equal(scores, want)
+
+
+def test_cnn_forward_zero_padding_correction():
+    # every binary convolution followed by the correction matrix == true zero padding
+    layers = synth.cnn_params()
+    x = synth.cnn_input(2)
+    net = nets.BinaryCNN(layers, 2, EPS, device=DEV, keep_first_pre=True, zero_pad=True)
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    want = _check_cnn(net, x, layers, np.arange(2), pad_value=0)
     assert np.array_equal(scores, want)
 
 

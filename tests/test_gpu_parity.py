@@ -295,6 +295,27 @@ def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad):
     assert np.array_equal(esp.bconv(xp, fp, C, stride, pad).cpu().numpy(), pre)
 
 
+# ------------------------------------------------------------------------------ zero-padding correction
+PADCORR_CASES = [(2, 5, 6, 128, 7, 3, 3, 1, 1), (2, 7, 5, 192, 5, 3, 3, 2, 1), (1, 6, 6, 100, 9, 3, 3, 1, 1),
+                 (2, 9, 7, 256, 64, 5, 3, 2, 2), (3, 32, 32, 128, 128, 3, 3, 1, 1), (2, 8, 8, 64, 12, 3, 3, 1, 0),
+                 (1, 3, 3, 64, 4, 3, 3, 1, 2), (2, 6, 7, 64, 6, 2, 2, 2, 1)]
+
+
+@pytest.mark.parametrize("B,H,W,C,L2,kh,kw,stride,pad", PADCORR_CASES)
+def test_pad_correction(B, H, W, C, L2, kh, kw, stride, pad):
+    # (-1)-padded convolution + correction matrix == zero-padded convolution (Sec. 5.2)
+    rng = np.random.default_rng(B + 10 * H + 100 * C + kh + 7)
+    x = _pm1(rng, (B, H, W, C))
+    f = _pm1(rng, (L2, kh, kw, C))
+    xp, fp = _packed_dev(x), _packed_dev(f)
+    corr = esp.pad_correction(fp, C, H, W, stride, pad)
+    want_corr = oracle.conv_pm1(np.zeros((1, H, W, C), dtype=np.int8), f, stride, pad, +1)[0]
+    assert np.array_equal(corr.cpu().numpy(), want_corr)
+    out = esp.bconv(xp, fp, C, stride, pad)
+    esp.add_pad_correction(out, corr, H, W, kh, kw, stride, pad)
+    assert np.array_equal(out.cpu().numpy(), oracle.conv_pm1(x, f, stride, pad, 0))
+
+
 # ------------------------------------------------------------------------------ bmaxpool
 @pytest.mark.parametrize("B,H,W,C,win,stride", [(1, 2, 2, 64, 2, 2), (2, 8, 8, 128, 2, 2), (3, 7, 9, 192, 2, 2),
                                                 (2, 6, 6, 100, 3, 1), (4, 32, 32, 128, 2, 2),
