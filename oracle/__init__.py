@@ -242,6 +242,37 @@ def conv_f64(x: np.ndarray, f: np.ndarray, stride: int = 1, pad: int = 0) -> np.
     return out
 
 
+def dense_u8(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """Sec. 4.3 (the product Eq. 3 re-assembles from bit-planes): x uint8 [M][K], w int8 +-1
+    [N][K] -> exact int32 [M][N]."""
+    lib = _load()
+    x = _c(x, np.uint8)
+    w = _c(w, np.int8)
+    M, K = x.shape
+    N, K2 = w.shape
+    assert K == K2
+    y = np.empty((M, N), dtype=np.int32)
+    lib.orc_dense_u8(_p(x), _p(w), _p(y), _i64(M), _i64(N), _i64(K))
+    return y
+
+
+def conv_u8(x: np.ndarray, f: np.ndarray, stride: int = 1, pad: int = 0) -> np.ndarray:
+    """Fixed-precision first conv layer: x uint8 NHWC, f int8 +-1 [L2][kh][kw][C], zero padding,
+    exact int32 [B][H2][W2][L2]."""
+    lib = _load()
+    x = _c(x, np.uint8)
+    f = _c(f, np.int8)
+    B, H, W, C = x.shape
+    L2, kh, kw, C2 = f.shape
+    assert C == C2
+    H2 = conv_out_size(H, kh, stride, pad)
+    W2 = conv_out_size(W, kw, stride, pad)
+    out = np.empty((B, H2, W2, L2), dtype=np.int32)
+    lib.orc_conv_u8(_p(x), _p(f), _p(out), _i64(B), _i64(H), _i64(W), _i64(C), _i64(L2),
+                    _i64(kh), _i64(kw), _i64(stride), _i64(pad))
+    return out
+
+
 def bn_sign(x: np.ndarray, bnp, eps: float) -> np.ndarray:
     """Batch-norm followed by Eq. 1; ``bnp`` = (gamma, beta, mean, var)."""
     return sign(bn(x, *bnp, eps))

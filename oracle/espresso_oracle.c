@@ -279,3 +279,46 @@ void orc_conv_f64(const float *in, const int8_t *filt, double *out,
                     out[((b * H2 + m) * W2 + n) * L2 + l2] = acc;
                 }
 }
+
+/* ------------------------------------------------------------------------ */
+/* First layer on fixed-precision input (Sec. 4.3): 8-bit unsigned inputs,   */
+/* +-1 weights, exact integer sums.  This is the plain product that Eq. 3    */
+/* re-assembles from bit-planes; the convolution pads with the value 0.      */
+/* ------------------------------------------------------------------------ */
+void orc_dense_u8(const uint8_t *x, const int8_t *w, int32_t *y, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)x[m * K + k] * (int32_t)w[n * K + k];
+            y[m * N + n] = acc;
+        }
+}
+
+void orc_conv_u8(const uint8_t *in, const int8_t *filt, int32_t *out,
+                 int64_t B, int64_t H, int64_t W, int64_t C, int64_t L2,
+                 int64_t kh, int64_t kw, int64_t stride, int64_t pad)
+{
+    const int64_t H2 = (H + 2 * pad - kh) / stride + 1;
+    const int64_t W2 = (W + 2 * pad - kw) / stride + 1;
+#pragma omp parallel for num_threads(g_threads) schedule(static) collapse(2)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t m = 0; m < H2; ++m)
+            for (int64_t n = 0; n < W2; ++n)
+                for (int64_t l2 = 0; l2 < L2; ++l2) {
+                    int32_t acc = 0;
+                    for (int64_t dy = 0; dy < kh; ++dy)
+                        for (int64_t dx = 0; dx < kw; ++dx) {
+                            const int64_t y = m * stride + dy - pad;
+                            const int64_t x = n * stride + dx - pad;
+                            if (y < 0 || y >= H || x < 0 || x >= W)
+                                continue; /* zero padding */
+                            for (int64_t c = 0; c < C; ++c)
+                                acc += (int32_t)in[((b * H + y) * W + x) * C + c] *
+                                       (int32_t)filt[((l2 * kh + dy) * kw + dx) * C + c];
+                        }
+                    out[((b * H2 + m) * W2 + n) * L2 + l2] = acc;
+                }
+}

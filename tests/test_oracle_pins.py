@@ -313,6 +313,40 @@ def test_float_dense_and_conv_against_library():
     np.testing.assert_allclose(oracle.conv_f64(img, f, 1, 1), ref, rtol=1e-13, atol=1e-13)
 
 
+# ------------------------------------------------------------------ fixed-precision first layer
+def test_u8_first_layer_against_library_and_eq3_bitplanes():
+    rng = np.random.default_rng(23)
+    x = rng.integers(0, 256, size=(4, 37), dtype=np.uint8)
+    x[0, :5] = [0, 255, 1, 128, 254]
+    w = _pm1(rng, (6, 37))
+    got = oracle.dense_u8(x, w)
+    assert np.array_equal(got, x.astype(np.int64) @ w.astype(np.int64).T)
+    # hand example: x = (3, 0, 255), w = (+, -, -): 3 - 0 - 255
+    assert oracle.dense_u8(np.array([[3, 0, 255]], dtype=np.uint8),
+                           np.array([[1, -1, -1]], dtype=np.int8)).tolist() == [[-252]]
+    # Eq. 3: the product is the weighted sum of the products of the 0/1 bit-planes
+    planes = [((x >> i) & 1).astype(np.int8) for i in range(8)]
+    eq3 = sum((1 << i) * oracle.dense_pm1(planes[i], w).astype(np.int64) for i in range(8))
+    assert np.array_equal(got, eq3)
+    # ... and each 0/1 plane product follows from the +-1 product of the plane read as +-1:
+    # p.w = ((2p-1).w + sum(w)) / 2
+    wsum = w.astype(np.int64).sum(axis=1)
+    for i in range(8):
+        pm = (2 * planes[i] - 1).astype(np.int8)
+        assert np.array_equal(2 * oracle.dense_pm1(planes[i], w), oracle.dense_pm1(pm, w) + wsum[None, :])
+
+    img = rng.integers(0, 256, size=(2, 6, 5, 3), dtype=np.uint8)
+    f = _pm1(rng, (4, 3, 3, 3))
+    ref = torch.nn.functional.conv2d(torch.from_numpy(img.astype(np.float64)).permute(0, 3, 1, 2),
+                                     torch.from_numpy(f.astype(np.float64)).permute(0, 3, 1, 2),
+                                     padding=1).permute(0, 2, 3, 1).numpy()
+    assert np.array_equal(oracle.conv_u8(img, f, 1, 1), ref.astype(np.int32))
+    assert np.array_equal(oracle.conv_u8(img, f, 2, 0),
+                          torch.nn.functional.conv2d(torch.from_numpy(img.astype(np.float64)).permute(0, 3, 1, 2),
+                                                     torch.from_numpy(f.astype(np.float64)).permute(0, 3, 1, 2),
+                                                     stride=2).permute(0, 2, 3, 1).numpy().astype(np.int32))
+
+
 # ------------------------------------------------------------------ network shapes
 def test_network_shapes_match_paper_footprints():
     # Sec. 6.2 / 6.3 print the float and packed footprints; the parameter counts of the
