@@ -313,6 +313,11 @@ def _networks(torch, esp, nets, synth, dev, only=None):
         x = torch.from_numpy(synth.mlp_input(batch)).to(dev)
         res["bmlp"][str(batch)] = time_net(net, x, batch, 50)
         del net
+        # same network with 8-bit input and the first layer evaluated by bit-planes (Eq. 3)
+        net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev, first_layer="bitplane")
+        x8 = (torch.from_numpy(synth.mlp_input(batch)).to(dev) * 256.0).clamp(0, 255).to(torch.uint8)
+        res["bmlp"][str(batch) + "_bitplane_first_layer"] = time_net(net, x8, batch, 50)
+        del net
     layers = synth.cnn_params()
     for batch in (1, 256):
         if only and only != ("bcnn", batch):

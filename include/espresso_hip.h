@@ -241,6 +241,36 @@ int esp_conv_f32_bn_sign_pack(const float *in, const float *filt, const float *t
                               int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
                               esp_stream stream);
 
+/* ------------------------------------------------------------------------- */
+/* Binary first layer on 8-bit fixed-precision input by bit-planes (Sec. 4.3, */
+/* Eq. 3; Sec. 6.2 "First-layer binary optimization": the input is split into */
+/* 8 rows and the products are recombined by a weighted sum).  Exact integer  */
+/* result  y[r][n] = sum_k x[r][k] * w[n][k],  x in 0..255, w = +-1.          */
+/*   bitplane_pack_u8:  x uint8 [outer][inner][k] ->                          */
+/*                      planes uint64 [outer][8][inner][ceil(k/64)],          */
+/*                      plane i holds bit i of every value (dense layer:      */
+/*                      inner = 1; NHWC image: outer = B, inner = H*W, k = C, */
+/*                      so that each plane is itself a packed NHWC image).    */
+/*   row_sums (load time): wsum int32 [N], wsum[n] = sum_k w[n][k] over the K */
+/*                      true values of row n of packed weights W              */
+/*                      [N][row_words] (for filters [L2][kh][kw][Cw]:         */
+/*                      row_words = kh*kw*Cw, K = kh*kw*C; tail bits are 0).  */
+/*   bitplane_combine:  d int32 [outer][8][inner][N], the esp_bgemm/esp_bconv */
+/*                      results of the 8 planes (a 0 bit counting as -1) ->   */
+/*                      y int32 [outer][inner][N] =                           */
+/*                      (sum_i 2^i d_i + 255 * wsum) / 2.                     */
+/* A pixel of value 0 is -1 in every plane, i.e. the -1 border of esp_bconv   */
+/* IS zero padding of the image.  k < 2^22.                                   */
+/* ------------------------------------------------------------------------- */
+int esp_bitplane_pack_u8(const uint8_t *x, uint64_t *planes, int64_t outer, int64_t inner,
+                         int64_t k, esp_stream stream);
+
+int esp_row_sums(const uint64_t *W, int32_t *wsum, int64_t N, int64_t row_words, int64_t K,
+                 esp_stream stream);
+
+int esp_bitplane_combine(const int32_t *d, const int32_t *wsum, int32_t *y, int64_t outer,
+                         int64_t inner, int64_t N, esp_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import bn, conv_f64, conv_pm1, dense_f64, dense_pm1, maxpool_pm1, sign
+from . import bn, conv_f64, conv_pm1, dense_f64, dense_pm1, dense_u8, maxpool_pm1, sign
 
 
 def _bn_sign(pre, bnp, eps):
@@ -36,7 +36,9 @@ def mlp_forward(x: np.ndarray, layers, eps: float, first_act: np.ndarray | None 
     act = None
     for i, layer in enumerate(layers):
         if i == 0:
-            pre = dense_f64(x, layer["w"])
+            # real-valued input (float first layer) or 8-bit fixed-precision input (Sec. 4.3:
+            # the exact integer product that the bit-plane evaluation of Eq. 3 reproduces)
+            pre = dense_u8(x, layer["w"]) if x.dtype == np.uint8 else dense_f64(x, layer["w"])
         else:
             pre = dense_pm1(act, layer["w"])
         rec = {"pre": pre}

@@ -25,6 +25,7 @@ EXPORTS = (
     "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
+    "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine",
 )
 
 _lib = None
@@ -67,6 +68,9 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
         l.esp_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
         l.esp_add_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
+        l.esp_bitplane_pack_u8.argtypes = [vp, vp, i64, i64, i64, vp]
+        l.esp_row_sums.argtypes = [vp, vp, i64, i64, i64, vp]
+        l.esp_bitplane_combine.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         for name in EXPORTS:
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
@@ -361,6 +365,45 @@ def conv_f32_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, thr: torch.Tensor
                                            _dev(sgn, torch.float32, "sgn"), _dev(out, PACKED, "out"), ppre,
                                            B, H, W, C, L2, kh, kw, stride, pad, _stream()),
            "esp_conv_f32_bn_sign_pack")
+    return out
+
+
+def bitplane_pack_u8(x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bitplane_pack_u8``: uint8 [outer][k] -> [outer][8][Kw], or uint8 NHWC [B][H][W][C] ->
+    [B][8][H][W][Cw] (each plane a packed NHWC image)."""
+    p = _dev(x, torch.uint8, "x")
+    k = x.shape[-1]
+    outer = x.shape[0]
+    inner = x.numel() // (outer * k) if outer and k else 1
+    if out is None:
+        out = torch.empty((outer, 8) + tuple(x.shape[1:-1]) + (words(k),), dtype=PACKED, device=x.device)
+    _check(lib().esp_bitplane_pack_u8(p, _dev(out, PACKED, "out"), outer, inner, k, _stream()),
+           "esp_bitplane_pack_u8")
+    return out
+
+
+def row_sums(w: torch.Tensor, k: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_row_sums``: packed weights [N][...] holding ``k`` true values per row -> int32 [N]."""
+    pw = _dev(w, PACKED, "w")
+    N = w.shape[0]
+    if out is None:
+        out = torch.empty((N,), dtype=torch.int32, device=w.device)
+    _check(lib().esp_row_sums(pw, _dev(out, torch.int32, "out"), N, w.numel() // N, int(k), _stream()),
+           "esp_row_sums")
+    return out
+
+
+def bitplane_combine(d: torch.Tensor, wsum: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bitplane_combine``: int32 [outer][8][...][N] -> int32 [outer][...][N]."""
+    pd = _dev(d, torch.int32, "d")
+    outer, N = d.shape[0], d.shape[-1]
+    if d.shape[1] != 8 or wsum.numel() != N:
+        raise ValueError("d must be [outer][8][...][N]")
+    inner = d.numel() // (outer * 8 * N) if outer else 1
+    if out is None:
+        out = torch.empty((outer,) + tuple(d.shape[2:]), dtype=torch.int32, device=d.device)
+    _check(lib().esp_bitplane_combine(pd, _dev(wsum, torch.int32, "wsum"), _dev(out, torch.int32, "out"),
+                                      outer, inner, N, _stream()), "esp_bitplane_combine")
     return out
 
 

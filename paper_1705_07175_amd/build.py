@@ -24,6 +24,7 @@ SOURCES = (
     ("pack.hip", ()),
     ("conv.hip", ()),
     ("float_layers.hip", ()),
+    ("bitplane.hip", ()),
     ("host.cpp", ("-ffp-contract=off",)),
 )
 

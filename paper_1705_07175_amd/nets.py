@@ -44,24 +44,42 @@ def _pack_weights(w_pm1: np.ndarray, device) -> torch.Tensor:
 class BinaryMLP:
     """Sec. 6.2 network: float dense, then binary dense layers, BN + sign in between."""
 
-    def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True):
+    def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True,
+                 first_layer: str = "float"):
         self.batch = batch
+        # "float": fp32 first layer on real-valued input; "bitplane": 8-bit input split into
+        # bit-planes and run through the binary product (Sec. 4.3, Eq. 3), exact in integers
+        self.first_layer = first_layer
         self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
         self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
         self.w1 = _dev_f32(layers[0]["w"], device)
-        self.bn = [_FoldedBN(l["bn"], eps, device, integer=(i > 0)) if l["bn"] is not None else None
+        bitplane = first_layer == "bitplane"
+        self.bn = [_FoldedBN(l["bn"], eps, device, integer=(i > 0 or bitplane)) if l["bn"] is not None else None
                    for i, l in enumerate(layers)]
         self.wp = [None] + [_pack_weights(l["w"], device) for l in layers[1:]]
+        if bitplane:
+            self.wp[0] = _pack_weights(layers[0]["w"], device)
+            self.wsum0 = esp.row_sums(self.wp[0], self.sizes[0])
+            self.planes = torch.empty((batch, 8, esp.words(self.sizes[0])), dtype=esp.PACKED, device=device)
+            self.plane_dots = torch.empty((batch, 8, self.sizes[1]), dtype=torch.int32, device=device)
         # pre-allocated activations
-        self.pre = [torch.empty((batch, self.sizes[1]), dtype=torch.float32, device=device)]
+        self.pre = [torch.empty((batch, self.sizes[1]), dtype=torch.int32 if bitplane else torch.float32,
+                                device=device)]
         self.pre += [torch.empty((batch, n), dtype=torch.int32, device=device) for n in self.sizes[2:]]
         self.act = [torch.empty((batch, esp.words(n)), dtype=esp.PACKED, device=device)
                     for n in self.sizes[1:-1]]
         torch.cuda.synchronize()
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
-        esp.dense_f32(x, self.w1, out=self.pre[0])
-        esp.bn_sign_pack_f32(self.pre[0], self.bn[0].thr, self.bn[0].sgn, out=self.act[0])
+        if self.first_layer == "bitplane":
+            esp.bitplane_pack_u8(x, out=self.planes)
+            esp.bgemm(self.planes.view(self.batch * 8, -1), self.wp[0], self.sizes[0],
+                      out=self.plane_dots.view(self.batch * 8, -1))
+            esp.bitplane_combine(self.plane_dots, self.wsum0, out=self.pre[0])
+            esp.bn_sign_pack(self.pre[0], self.bn[0].thr, self.bn[0].flip, out=self.act[0])
+        else:
+            esp.dense_f32(x, self.w1, out=self.pre[0])
+            esp.bn_sign_pack_f32(self.pre[0], self.bn[0].thr, self.bn[0].sgn, out=self.act[0])
         self._binary_layers()
         return self.pre[-1]
 

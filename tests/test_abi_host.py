@@ -71,6 +71,11 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_pad_correction(p, p, 4, 4, 64, 8, 7, 3, 1, 1, None) == -3
     assert lib.esp_add_pad_correction(None, p, 1, 4, 4, 8, 3, 3, 1, 1, None) == -1
     assert lib.esp_add_pad_correction(p, p, 0, 4, 4, 8, 3, 3, 1, 1, None) == 0
+    assert lib.esp_bitplane_pack_u8(p, None, 2, 1, 64, None) == -1
+    assert lib.esp_bitplane_pack_u8(p, p, 2, 1, 1 << 22, None) == -3
+    assert lib.esp_row_sums(None, p, 4, 1, 64, None) == -1
+    assert lib.esp_row_sums(p, p, 4, 1, 65, None) == -3
+    assert lib.esp_bitplane_combine(p, p, None, 2, 1, 4, None) == -1
     assert lib.esp_conv_f32_bn_sign_pack(p, p, p, p, None, None, 1, 4, 4, 3, 8, 3, 3, 1, 1, None) == -1
     assert lib.esp_bn_fold(None, p, p, p, 1e-4, 4, p, p) == -1
 

@@ -63,6 +63,21 @@ def test_mlp_forward(batch):
     assert np.array_equal(scores, ref[3]["pre"])
 
 
+@pytest.mark.parametrize("batch", [1, 70])
+def test_mlp_forward_bitplane_first_layer(batch):
+    # 8-bit input, first layer by bit-planes (Eq. 3): integer everywhere, so the whole network
+    # is bit-exact against the oracle with no tolerance band
+    layers = synth.mlp_params()
+    x = np.minimum(255, np.floor(synth.mlp_input(batch) * 256.0)).astype(np.uint8)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=False, first_layer="bitplane")
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    ref = onets.mlp_forward(x, layers, EPS)
+    assert np.array_equal(net.pre[0].cpu().numpy(), ref[0]["pre"])
+    for i in (0, 1, 2):
+        assert np.array_equal(esp.packed_to_numpy(net.act[i]), oracle.pack_bits(ref[i]["act"]))
+    assert np.array_equal(scores, ref[3]["pre"])
+
+
 def test_mlp_batch1024_sampled_rows():
     # full-size batch on the GPU; the oracle recomputes a sample of the (independent) rows
     layers = synth.mlp_params()

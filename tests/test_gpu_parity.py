@@ -316,6 +316,40 @@ def test_pad_correction(B, H, W, C, L2, kh, kw, stride, pad):
     assert np.array_equal(out.cpu().numpy(), oracle.conv_pm1(x, f, stride, pad, 0))
 
 
+# ------------------------------------------------------------------------------ bit-plane first layer
+@pytest.mark.parametrize("M,N,K", [(1, 10, 64), (3, 70, 100), (64, 4096, 784), (9, 130, 1000), (1, 4096, 784)])
+def test_bitplane_dense(M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    x = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    x[0, : min(K, 4)] = [0, 255, 1, 128][: min(K, 4)]
+    w = _pm1(rng, (N, K))
+    wp = _packed_dev(w)
+    planes = esp.bitplane_pack_u8(torch.from_numpy(x).to(DEV))
+    assert planes.shape == (M, 8, (K + 63) // 64)
+    want_planes = np.stack([oracle.pack_bits((((x >> i) & 1).astype(np.int8) * 2 - 1)) for i in range(8)], axis=1)
+    assert np.array_equal(esp.packed_to_numpy(planes), want_planes)
+    wsum = esp.row_sums(wp, K)
+    assert np.array_equal(wsum.cpu().numpy(), w.astype(np.int64).sum(axis=1))
+    d = esp.bgemm(planes.reshape(M * 8, -1), wp, K).reshape(M, 8, N)
+    y = esp.bitplane_combine(d, wsum)
+    assert np.array_equal(y.cpu().numpy(), oracle.dense_u8(x, w))
+
+
+@pytest.mark.parametrize("B,H,W,C,L2", [(2, 32, 32, 3, 128), (3, 6, 5, 3, 20), (1, 8, 8, 70, 9)])
+def test_bitplane_conv(B, H, W, C, L2):
+    rng = np.random.default_rng(B + H + C + L2)
+    x = rng.integers(0, 256, size=(B, H, W, C), dtype=np.uint8)
+    f = _pm1(rng, (L2, 3, 3, C))
+    fp = _packed_dev(f)
+    planes = esp.bitplane_pack_u8(torch.from_numpy(x).to(DEV))          # [B][8][H][W][Cw]
+    assert planes.shape == (B, 8, H, W, (C + 63) // 64)
+    wsum = esp.row_sums(fp, 9 * C)      # every tap is padded to whole words; tail bits are 0
+    assert np.array_equal(wsum.cpu().numpy(), f.reshape(L2, -1).astype(np.int64).sum(axis=1))
+    d = esp.bconv(planes.reshape(B * 8, H, W, -1), fp, C, 1, 1).reshape(B, 8, H, W, L2)
+    y = esp.bitplane_combine(d, wsum)
+    assert np.array_equal(y.cpu().numpy(), oracle.conv_u8(x, f, 1, 1))
+
+
 # ------------------------------------------------------------------------------ bmaxpool
 @pytest.mark.parametrize("B,H,W,C,win,stride", [(1, 2, 2, 64, 2, 2), (2, 8, 8, 128, 2, 2), (3, 7, 9, 192, 2, 2),
                                                 (2, 6, 6, 100, 3, 1), (4, 32, 32, 128, 2, 2),
