@@ -91,6 +91,16 @@ int esp_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C,
               int64_t M, int64_t N, int64_t K, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
+/* bgemm_mfma: the same product as esp_bgemm (identical int32 results),       */
+/* evaluated on the matrix cores instead of XOR + popcount: the packed bits   */
+/* are expanded in registers to 4-bit floating-point operands of the          */
+/* block-scaled MFMA and accumulated exactly in fp32.  A measured alternative */
+/* for the dense contraction; K < 2^24.                                       */
+/* ------------------------------------------------------------------------- */
+int esp_bgemm_mfma(const uint64_t *A, const uint64_t *B, int32_t *C,
+                   int64_t M, int64_t N, int64_t K, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
 /* unroll: packed im2col (Sec. 5.2 "Convolutional layers", Fig. 3).           */
 /*   in   uint64 [B][H][W][Cw]                  Cw = ceil(C/64)               */
 /*   out  uint64 [B*H2*W2][kh*kw*Cw]            H2 = (H+2*pad-kh)/stride+1    */

@@ -25,7 +25,7 @@ EXPORTS = (
     "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
-    "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine",
+    "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma",
 )
 
 _lib = None
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bitplane_pack_u8.argtypes = [vp, vp, i64, i64, i64, vp]
         l.esp_row_sums.argtypes = [vp, vp, i64, i64, i64, vp]
         l.esp_bitplane_combine.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        l.esp_bgemm_mfma.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         for name in EXPORTS:
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
@@ -135,6 +136,19 @@ def bgemm(a: torch.Tensor, b: torch.Tensor, k: int, out: torch.Tensor | None = N
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=a.device)
     _check(lib().esp_bgemm(pa, pb, _dev(out, torch.int32, "out"), M, N, int(k), _stream()), "esp_bgemm")
+    return out
+
+
+def bgemm_mfma(a: torch.Tensor, b: torch.Tensor, k: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_bgemm_mfma``: same result as :func:`bgemm`, computed on the matrix cores."""
+    pa, pb = _dev(a, PACKED, "a"), _dev(b, PACKED, "b")
+    M, N = a.shape[0], b.shape[0]
+    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != words(k) or b.shape[1] != words(k):
+        raise ValueError("a and b must be [rows][ceil(k/64)]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _check(lib().esp_bgemm_mfma(pa, pb, _dev(out, torch.int32, "out"), M, N, int(k), _stream()),
+           "esp_bgemm_mfma")
     return out
 
 

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(HERE, "libespresso_hip.so")
 # every operation, hence no fused multiply-add there.
 SOURCES = (
     ("bgemm.hip", ()),
+    ("bgemm_mfma.hip", ()),
     ("pack.hip", ()),
     ("conv.hip", ()),
     ("float_layers.hip", ()),

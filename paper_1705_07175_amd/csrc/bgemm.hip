@@ -17,6 +17,7 @@
 //  * bgemv_kernel       -- small M (matrix-vector, Sec. 6.2 "Optimized kernels"):
 //    bandwidth-bound streaming of B with the few A rows held in LDS.
 #include "esp_internal.h"
+#include "tile_sources.h"
 
 namespace esp {
 
@@ -25,90 +26,6 @@ namespace esp {
 // ---------------------------------------------------------------------------------
 constexpr int kKG = 8;        // 16-byte k-groups per LDS stage: 8 * 128 bits = 1024 bits of K
 constexpr int kStageDw = 32;  // dwords of K per row per stage
-constexpr int kXcd = 8;       // XCDs (one L2 each); blocks are dealt to them round-robin
-constexpr int kGroupM = 8;    // tile rows walked together so A and B slabs stay in one L2
-
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
-
-// 16 bytes of row `p` starting at dword kd of a row that is row_dw dwords long.
-template <bool VEC16>
-__device__ __forceinline__ uint4 load_chunk(const uint32_t *__restrict__ p, int kd, int row_dw)
-{
-    uint4 v = zero4();
-    if (VEC16) {
-        if (kd < row_dw)
-            v = *reinterpret_cast<const uint4 *>(p + kd);
-    } else {
-        if (kd < row_dw) {
-            const uint2 lo = *reinterpret_cast<const uint2 *>(p + kd);
-            v.x = lo.x;
-            v.y = lo.y;
-        }
-        if (kd + 2 < row_dw) {
-            const uint2 hi = *reinterpret_cast<const uint2 *>(p + kd + 2);
-            v.z = hi.x;
-            v.w = hi.y;
-        }
-    }
-    return v;
-}
-
-// ---- A operand: rows of a packed matrix ------------------------------------------
-template <bool VEC16>
-struct MatrixA {
-    const uint32_t *base;
-    int rows;    // M
-    int row_dw;  // dwords per row
-    struct Row { const uint32_t *p; };
-    __device__ __forceinline__ Row row(int r) const
-    {
-        return Row{r < rows ? base + (int64_t)r * row_dw : nullptr};
-    }
-    struct Step {};
-    __device__ __forceinline__ Step step(int /*kd*/) const { return Step{}; }
-    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &, int kd) const
-    {
-        return r.p ? load_chunk<VEC16>(r.p, kd, row_dw) : zero4();
-    }
-};
-
-// ---- A operand: the lowered matrix of a convolution, gathered on the fly ----------
-// Row r = (b*H2 + m)*W2 + n is the sliding volume of output pixel (b, m, n); dword kd of
-// that row is dword kd % cdw of input pixel (m*s - p + dy, n*s - p + dx) with
-// tap = kd / cdw = dy*kw + dx; pixels outside the image read as zero words (= -1).
-// Needs cdw % 4 == 0 (C a multiple of 128) so that a 16-byte chunk never straddles taps.
-struct ConvA {
-    const uint32_t *in;
-    int rows;    // B*H2*W2
-    int row_dw;  // kh*kw*cdw
-    int H, W, cdw, stride, pad;
-    FastDiv d_w2, d_h2, d_cdw, d_kw;
-    struct Row { int64_t img; int y0, x0; };   // img < 0: row beyond M
-    __device__ __forceinline__ Row row(int r) const
-    {
-        if (r >= rows)
-            return Row{-1, 0, 0};
-        const uint32_t bm = fd_div((uint32_t)r, d_w2);
-        const uint32_t n = (uint32_t)r - bm * d_w2.div;
-        const uint32_t b = fd_div(bm, d_h2);
-        const uint32_t m = bm - b * d_h2.div;
-        return Row{(int64_t)b * H * W, (int)(m * stride) - pad, (int)(n * stride) - pad};
-    }
-    struct Step { int dy, dx, c; };
-    __device__ __forceinline__ Step step(int kd) const
-    {
-        const uint32_t tap = fd_div((uint32_t)kd, d_cdw);
-        const uint32_t dy = fd_div(tap, d_kw);
-        return Step{(int)dy, (int)(tap - dy * d_kw.div), (int)((uint32_t)kd - tap * d_cdw.div)};
-    }
-    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &s, int kd) const
-    {
-        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
-        if (r.img < 0 || kd >= row_dw || y < 0 || y >= H || x < 0 || x >= W)
-            return zero4();
-        return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)y * W + x) * cdw + s.c);
-    }
-};
 
 // ---- epilogue: int32 dot products ---------------------------------------------------
 struct StoreDots {
@@ -263,19 +180,9 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
     __shared__ uint4 As[kKG][BM + 1];
     __shared__ uint4 Bs[kKG][BN + 1];
 
-    // Block -> tile: consecutive block ids land on different XCDs, so give every XCD
-    // a contiguous range of tiles and walk it in groups of kGroupM tile rows.
-    const int total_tiles = tiles_m * tiles_n;
-    const int pid = blockIdx.x;
-    const int tile = (pid % kXcd) * tiles_per_xcd + pid / kXcd;
-    if (tile >= total_tiles)
+    int tm, tn;
+    if (!block_to_tile(tiles_m, tiles_n, tiles_per_xcd, &tm, &tn))
         return;
-    const int group_size = kGroupM * tiles_n;
-    const int first_m = (tile / group_size) * kGroupM;
-    const int gm = min(tiles_m - first_m, kGroupM);
-    const int in_group = tile % group_size;
-    const int tm = first_m + in_group % gm;
-    const int tn = in_group / gm;
     const int m0 = tm * BM;
     const int n0 = tn * BN;
 

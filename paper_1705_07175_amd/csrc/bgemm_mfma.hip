@@ -1,0 +1,304 @@
+// Binary matrix product on the matrix cores (measured alternative to the XOR-popcount
+// kernel for the dense contraction of Sec. 4.2, Eq. 2 of arXiv 1705.07175).
+//
+// gfx950's block-scaled MFMA takes 4-bit floating-point (E2M1) operands at twice the rate of
+// 8-bit ones.  A packed bit needs no real conversion to become such an operand:
+//   * A bits are used as {0, v}: masking a source dword with 0x11111111 << j leaves, in every
+//     nibble, either 0 or the E2M1 pattern 1, 2 or 4 = 0.5, 1.0 or 2.0; the instruction's
+//     per-block scale (2^1, 2^0, 2^-1) turns each of them into exactly 1.  One AND per
+//     operand dword (bit 3 of a nibble is the sign bit, so j = 3 takes a shift first).
+//   * B bits are used as +-1: the bit is moved to the nibble's sign position and combined
+//     with the magnitude pattern of 1.0 ((x & 0x88888888) ^ 0xAAAAAAAA: bit 1 -> +1.0,
+//     bit 0 -> -1.0).
+// Any permutation of k is allowed as long as both operands use the same one, so the four
+// masks j = 0..3 of one source dword simply feed four successive MFMA calls.
+// With a in {0,1} and b in {-1,+1} the accumulator holds r = sum_k a_k b_k exactly (fp32,
+// |r| <= K < 2^24) and the +-1 dot product is  2 r - sum_k b_k : a 0 bit of A (= -1, also the
+// -1 border of a convolution) contributes -b_k.  sum_k b_k = 2 popcount(B row) - K is
+// accumulated by the same lanes that unpack B, whose column is also their column of C.
+//
+// Tile: 256 threads = 2 x 2 waves, each wave 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32
+// (v_mfma_scale_f32_32x32x64_f8f6f4), fed from LDS slabs of packed rows in the same
+// 16-byte k-group layout as the XOR-popcount kernel.
+#include "esp_internal.h"
+#include "tile_sources.h"
+
+namespace esp {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaBM = 256, kMfmaBN = 128;   // block tile
+constexpr int kMfmaKG = 4;                     // 16-byte k-groups per LDS stage (512 bits of K)
+constexpr int kMaxMfmaK = 1 << 24;             // fp32 accumulation stays exact
+
+// E8M0 scale bytes: 2^(s - 127)
+constexpr int kScale2 = 128, kScale1 = 127, kScaleHalf = 126;
+
+template <int J>
+__device__ __forceinline__ v8i encode_a(const uint4 x)
+{
+    v8i r;
+    if (J < 3) {
+        const uint32_t m = 0x11111111u << J;
+        r[0] = (int)(x.x & m);
+        r[1] = (int)(x.y & m);
+        r[2] = (int)(x.z & m);
+        r[3] = (int)(x.w & m);
+    } else {
+        r[0] = (int)((x.x >> 1) & 0x44444444u);
+        r[1] = (int)((x.y >> 1) & 0x44444444u);
+        r[2] = (int)((x.z >> 1) & 0x44444444u);
+        r[3] = (int)((x.w >> 1) & 0x44444444u);
+    }
+    r[4] = r[5] = r[6] = r[7] = 0;   // unused by 4-bit operands
+    return r;
+}
+
+template <int J>
+__device__ __forceinline__ v8i encode_b(const uint4 x)
+{
+    v8i r;
+    r[0] = (int)(((x.x << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
+    r[1] = (int)(((x.y << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
+    r[2] = (int)(((x.z << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
+    r[3] = (int)(((x.w << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
+    r[4] = r[5] = r[6] = r[7] = 0;
+    return r;
+}
+
+template <int J>
+__device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&xb)[2], v16f (&acc)[4][2])
+{
+    constexpr int sa = J == 0 ? kScale2 : (J == 1 ? kScale1 : kScaleHalf);
+    const v8i b0 = encode_b<J>(xb[0]);
+    const v8i b1 = encode_b<J>(xb[1]);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        const v8i a = encode_a<J>(xa[f]);
+        acc[f][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b0, acc[f][0], 4, 4, 0, sa, 0, kScale1);
+        acc[f][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b1, acc[f][1], 4, 4, 0, sa, 0, kScale1);
+    }
+}
+
+struct MfmaOut {
+    int32_t *C;             // int32 dots [M][N], or
+    uint64_t *bits;         // packed signs [M][Nw]
+    const int32_t *thr;
+    const uint64_t *flip;
+    int Nw;
+};
+
+template <class ASrc, bool VEC16B, bool BITS>
+__global__ __launch_bounds__(256, 2)
+void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const MfmaOut o, int M, int N,
+                       int K_true, int row_dw, int tiles_m, int tiles_n, int tiles_per_xcd)
+{
+    constexpr int BM = kMfmaBM, BN = kMfmaBN, KG = kMfmaKG, NT = 256;
+    constexpr int STAGE_DW = KG * 4;
+    __shared__ uint4 As[KG][BM + 1];
+    __shared__ uint4 Bs[KG][BN + 1];
+
+    int tm, tn;
+    if (!block_to_tile(tiles_m, tiles_n, tiles_per_xcd, &tm, &tn))
+        return;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x;
+    const int lane = tid % kWave;
+    const int wave = tid / kWave;
+    const int wm = (wave / 2) * 128;   // wave's row offset inside the block tile
+    const int wn = (wave % 2) * 64;    // wave's column offset
+
+    // loader: chunk idx = tid + i*NT -> (row idx / KG, k-group idx % KG); NT % KG == 0
+    constexpr int A_CH = BM * KG / NT;   // 4
+    constexpr int B_CH = BN * KG / NT;   // 2
+    const int kg_mine = tid % KG;
+    typename ASrc::Row arow[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+        arow[i] = asrc.row(m0 + (tid + i * NT) / KG);
+    const uint32_t *brow[B_CH];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+        const int n = n0 + (tid + i * NT) / KG;
+        brow[i] = n < N ? B + (int64_t)n * row_dw : nullptr;
+    }
+    uint4 pa[A_CH], pb[B_CH];
+    auto prefetch = [&](int stage) {
+        const int kd = stage * STAGE_DW + kg_mine * 4;
+        const typename ASrc::Step st = asrc.step(kd);
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i)
+            pa[i] = asrc.fetch(arow[i], st, kd);
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i)
+            pb[i] = brow[i] ? load_chunk<VEC16B>(brow[i], kd, row_dw) : zero4();
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i)
+            As[kg_mine][(tid + i * NT) / KG] = pa[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i)
+            Bs[kg_mine][(tid + i * NT) / KG] = pb[i];
+    };
+
+    v16f acc[4][2];
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[f][g][r] = 0.0f;
+    int ones[2] = {0, 0};   // set bits of this lane's share of its two B columns
+
+    // operand lane mapping of the 32x32x64 MFMA: row/column = lane % 32, k half = lane / 32
+    const int lr = lane % 32, half = lane / 32;
+    const int stages = (row_dw + STAGE_DW - 1) / STAGE_DW;
+    prefetch(0);
+    for (int s = 0; s < stages; ++s) {
+        commit();
+        __syncthreads();
+        if (s + 1 < stages)
+            prefetch(s + 1);
+#pragma unroll
+        for (int step = 0; step < KG / 2; ++step) {
+            const int kg = 2 * step + half;
+            uint4 xa[4], xb[2];
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+                xa[f] = As[kg][wm + f * 32 + lr];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                xb[g] = Bs[kg][wn + g * 32 + lr];
+                ones[g] += __popc(xb[g].x) + __popc(xb[g].y) + __popc(xb[g].z) + __popc(xb[g].w);
+            }
+            mfma_group<0>(xa, xb, acc);
+            mfma_group<1>(xa, xb, acc);
+            mfma_group<2>(xa, xb, acc);
+            mfma_group<3>(xa, xb, acc);
+        }
+        __syncthreads();
+    }
+
+    // sum_k b_k of the lane's two columns: both k halves together
+    int bsum[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int tot = ones[g] + __shfl_xor(ones[g], 32, kWave);
+        bsum[g] = 2 * tot - K_true;
+    }
+
+    // result layout of a 32x32 block: lane -> column lane % 32; register r -> row
+    // 8 * (r / 4) + 4 * (lane / 32) + r % 4
+    if (BITS) {
+        // one 64-column word per row of the wave tile: the comparison masks of the two
+        // column blocks are its two halves (lanes 0-31: row R, lanes 32-63: row R + 4)
+        int lim[2];
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const int col = n0 + wn + g * 32 + lr;
+            lim[g] = col < N ? o.thr[col] : 0x7fffffff;   // never reached beyond N: tail bits 0
+        }
+        uint64_t mine[2] = {0, 0};   // lane L keeps the words of wave-tile rows L and 64 + L
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint64_t m0b = __ballot(2 * (int)acc[f][0][r] - bsum[0] >= lim[0]);
+                const uint64_t m1b = __ballot(2 * (int)acc[f][1][r] - bsum[1] >= lim[1]);
+                const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
+                const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
+                const int R = f * 32 + 8 * (r / 4) + r % 4;                          // compile-time
+                if (lane == R % 64)
+                    mine[R / 64] = w_lo;
+                if (lane == (R + 4) % 64)
+                    mine[(R + 4) / 64] = w_hi;
+            }
+        const int w = (n0 + wn) >> 6;
+        if (w < o.Nw) {
+            const uint64_t fl = o.flip[w];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = m0 + wm + h * 64 + lane;
+                if (row < M)
+                    o.bits[(int64_t)row * o.Nw + w] = mine[h] ^ fl;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4;
+                if (row >= M)
+                    continue;
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const int col = n0 + wn + g * 32 + lr;
+                    if (col < N)
+                        o.C[(int64_t)row * N + col] = 2 * (int)acc[f][g][r] - bsum[g];
+                }
+            }
+    }
+}
+
+template <class ASrc, bool VEC16B>
+static int launch_mfma(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_dw, hipStream_t stream)
+{
+    const int tiles_m = (int)ceil_div(M, kMfmaBM);
+    const int tiles_n = (int)ceil_div(N, kMfmaBN);
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    if (total > (1ll << 30))
+        return ESP_ESHAPE;
+    const int per_xcd = (int)ceil_div(total, kXcd);
+    const dim3 grid((unsigned)(per_xcd * kXcd));
+    if (o.bits)
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true>), grid, dim3(256), 0, stream, asrc, b, o,
+                           (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n, per_xcd);
+    else
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, false>), grid, dim3(256), 0, stream, asrc, b, o,
+                           (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n, per_xcd);
+    return launch_status();
+}
+
+int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const int32_t *thr,
+                      const uint64_t *flip, uint64_t *bits, int64_t M, int64_t N, int64_t K_true,
+                      int64_t row_words, hipStream_t stream)
+{
+    if (M == 0)
+        return ESP_OK;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29) || K_true >= kMaxMfmaK)
+        return ESP_ESHAPE;
+    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64)};
+    const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
+    const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
+    const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
+    const int row_dw = (int)(row_words * 2);
+    if (vec16)
+        return launch_mfma<MatrixA<true>, true>(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw,
+                                                stream);
+    return launch_mfma<MatrixA<false>, false>(MatrixA<false>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw,
+                                              stream);
+}
+
+} // namespace esp
+
+extern "C" int esp_bgemm_mfma(const uint64_t *A, const uint64_t *B, int32_t *C,
+                              int64_t M, int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (K >= kMaxMfmaK)
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!A || !B || !C)
+        return ESP_EINVAL;
+    if (!aligned(A, 8) || !aligned(B, 8) || !aligned(C, 4))
+        return ESP_EALIGN;
+    return bgemm_mfma_launch(A, B, C, nullptr, nullptr, nullptr, M, N, K, ceil_div(K, 64), as_stream(stream));
+}

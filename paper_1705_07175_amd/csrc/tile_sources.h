@@ -1,0 +1,114 @@
+// Operand sources shared by the tiled binary-product kernels: 16-byte chunks of packed rows
+// read either from a packed matrix or, for convolutions (arXiv 1705.07175, Sec. 5.2
+// "Convolutional layers", Fig. 3), gathered straight from the packed NHWC input so that the
+// lowered matrix never exists in memory.
+#pragma once
+
+#include "esp_internal.h"
+
+namespace esp {
+
+constexpr int kXcd = 8;       // XCDs (one L2 each); blocks are dealt to them round-robin
+constexpr int kGroupM = 8;    // tile rows walked together so A and B slabs stay in one L2
+
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// 16 bytes of row `p` starting at dword kd of a row that is row_dw dwords long.
+template <bool VEC16>
+__device__ __forceinline__ uint4 load_chunk(const uint32_t *__restrict__ p, int kd, int row_dw)
+{
+    uint4 v = zero4();
+    if (VEC16) {
+        if (kd < row_dw)
+            v = *reinterpret_cast<const uint4 *>(p + kd);
+    } else {
+        if (kd < row_dw) {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(p + kd);
+            v.x = lo.x;
+            v.y = lo.y;
+        }
+        if (kd + 2 < row_dw) {
+            const uint2 hi = *reinterpret_cast<const uint2 *>(p + kd + 2);
+            v.z = hi.x;
+            v.w = hi.y;
+        }
+    }
+    return v;
+}
+
+// ---- A operand: rows of a packed matrix ------------------------------------------
+template <bool VEC16>
+struct MatrixA {
+    const uint32_t *base;
+    int rows;    // M
+    int row_dw;  // dwords per row
+    struct Row { const uint32_t *p; };
+    __device__ __forceinline__ Row row(int r) const
+    {
+        return Row{r < rows ? base + (int64_t)r * row_dw : nullptr};
+    }
+    struct Step {};
+    __device__ __forceinline__ Step step(int /*kd*/) const { return Step{}; }
+    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &, int kd) const
+    {
+        return r.p ? load_chunk<VEC16>(r.p, kd, row_dw) : zero4();
+    }
+};
+
+// ---- A operand: the lowered matrix of a convolution, gathered on the fly ----------
+// Row r = (b*H2 + m)*W2 + n is the sliding volume of output pixel (b, m, n); dword kd of
+// that row is dword kd % cdw of input pixel (m*s - p + dy, n*s - p + dx) with
+// tap = kd / cdw = dy*kw + dx; pixels outside the image read as zero words (= -1).
+// Needs cdw % 4 == 0 (C a multiple of 128) so that a 16-byte chunk never straddles taps.
+struct ConvA {
+    const uint32_t *in;
+    int rows;    // B*H2*W2
+    int row_dw;  // kh*kw*cdw
+    int H, W, cdw, stride, pad;
+    FastDiv d_w2, d_h2, d_cdw, d_kw;
+    struct Row { int64_t img; int y0, x0; };   // img < 0: row beyond M
+    __device__ __forceinline__ Row row(int r) const
+    {
+        if (r >= rows)
+            return Row{-1, 0, 0};
+        const uint32_t bm = fd_div((uint32_t)r, d_w2);
+        const uint32_t n = (uint32_t)r - bm * d_w2.div;
+        const uint32_t b = fd_div(bm, d_h2);
+        const uint32_t m = bm - b * d_h2.div;
+        return Row{(int64_t)b * H * W, (int)(m * stride) - pad, (int)(n * stride) - pad};
+    }
+    struct Step { int dy, dx, c; };
+    __device__ __forceinline__ Step step(int kd) const
+    {
+        const uint32_t tap = fd_div((uint32_t)kd, d_cdw);
+        const uint32_t dy = fd_div(tap, d_kw);
+        return Step{(int)dy, (int)(tap - dy * d_kw.div), (int)((uint32_t)kd - tap * d_cdw.div)};
+    }
+    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &s, int kd) const
+    {
+        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
+        if (r.img < 0 || kd >= row_dw || y < 0 || y >= H || x < 0 || x >= W)
+            return zero4();
+        return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)y * W + x) * cdw + s.c);
+    }
+};
+
+// Block id -> (tile row, tile column).  Consecutive block ids land on different XCDs, so
+// every XCD gets a contiguous range of tiles, walked in groups of kGroupM tile rows.
+// Returns false for the padding blocks beyond the last tile.
+__device__ __forceinline__ bool block_to_tile(int tiles_m, int tiles_n, int tiles_per_xcd, int *tm, int *tn)
+{
+    const int pid = blockIdx.x;
+    const int tile = (pid % kXcd) * tiles_per_xcd + pid / kXcd;
+    if (tile >= tiles_m * tiles_n)
+        return false;
+    const int group_size = kGroupM * tiles_n;
+    const int first_m = (tile / group_size) * kGroupM;
+    const int gm = min(tiles_m - first_m, kGroupM);
+    const int in_group = tile % group_size;
+    *tm = first_m + in_group % gm;
+    *tn = in_group / gm;
+    return true;
+}
+
+} // namespace esp

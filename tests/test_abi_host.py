@@ -46,6 +46,8 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bgemm(p, p, p, 4, 4, 1 << 30, None) == -3
     assert lib.esp_bgemm(p + 4, p, p, 4, 4, 64, None) == -2
     assert lib.esp_bgemm(None, None, None, 0, 4, 64, None) == 0        # empty M is a no-op
+    assert lib.esp_bgemm_mfma(None, p, p, 4, 4, 64, None) == -1
+    assert lib.esp_bgemm_mfma(p, p, p, 4, 4, 1 << 24, None) == -3
     assert lib.esp_pack_f32(None, p, 3, 64, None) == -1
     assert lib.esp_pack_f32(p, p + 4, 3, 64, None) == -2
     assert lib.esp_pack_f32(p, p, 0, 64, None) == 0

@@ -85,6 +85,21 @@ def test_bgemm(M, N, K):
     assert np.array_equal(got, oracle.dense_pm1(a, b))
 
 
+@pytest.mark.parametrize("M,N,K", BGEMM_SHAPES + [(256, 128, 512), (300, 200, 1000), (513, 130, 4160)])
+def test_bgemm_mfma(M, N, K):
+    rng = np.random.default_rng(M * 7919 + N * 104729 + K + 1)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    got = esp.bgemm_mfma(_packed_dev(a), _packed_dev(b), K).cpu().numpy()
+    assert np.array_equal(got, oracle.dense_pm1(a, b))
+
+
+@pytest.mark.parametrize("n", [2048, 8192])
+def test_bgemm_mfma_config5_square_sampled(n):
+    a, b = synth.config5_square(n)
+    c = esp.bgemm_mfma(_packed_dev(a), _packed_dev(b), n).cpu().numpy()
+    _check_sampled(a, b, c, np.random.default_rng(n + 1))
+
+
 def test_bgemm_config1():
     a, b = synth.config1()
     got = esp.bgemm(_packed_dev(a), _packed_dev(b), 1024).cpu().numpy()
