@@ -335,10 +335,11 @@ def _networks(torch, esp, nets, synth, dev, only=None):
     for batch in (1, 256):
         if only and only != ("bcnn", batch):
             continue
-        net = nets.BinaryCNN(layers, batch, synth.BN_EPS, device=dev)
         x = torch.from_numpy(synth.cnn_input(batch)).to(dev)
-        res["bcnn"][str(batch)] = time_net(net, x, batch, 30)
-        del net
+        for key, engine in ((str(batch), esp.ENGINE_XOR_POPCOUNT), (str(batch) + "_mfma_engine", esp.ENGINE_MFMA)):
+            net = nets.BinaryCNN(layers, batch, synth.BN_EPS, device=dev, engine=engine)
+            res["bcnn"][key] = time_net(net, x, batch, 30)
+            del net
     res["paper_context"] = "batch 1 on a GTX 960: BMLP 0.26 ms (Table 2), BCNN 1.0 ms (Table 3)"
     return res
 

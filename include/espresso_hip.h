@@ -58,6 +58,13 @@ enum esp_status {
     ESP_ELAUNCH = -5     /* the HIP runtime refused a launch                      */
 };
 
+/* Which units evaluate the binary contraction of the fused / convolution     */
+/* entry points that take an `engine` argument.  Results are identical.       */
+enum esp_engine {
+    ESP_ENGINE_XOR_POPCOUNT = 0, /* vector ALU: v_xor + v_bcnt (the paper's XNOR/bit-count) */
+    ESP_ENGINE_MFMA = 1          /* matrix cores: bits expanded to 4-bit float operands      */
+};
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char *esp_strerror(int status);
 
@@ -169,16 +176,21 @@ int esp_bn_sign_pack(const int32_t *x, const int32_t *thr, const uint64_t *flip,
 /*   bconv_bn_sign_pack:  in [B][H][W][Cw], filt [L2][kh][kw][Cw]             */
 /*                        -> out uint64 [B][H2][W2][ceil(L2/64)]              */
 /*   thr int32 [N or L2], flip uint64 [ceil(N or L2 / 64)]; workspace as for  */
-/*   esp_bconv.                                                               */
+/*   esp_bconv; engine is an esp_engine (ESP_EINVAL otherwise; the MFMA       */
+/*   engine needs K < 2^24).  esp_bconv_mfma is esp_bconv on the matrix cores.*/
 /* ------------------------------------------------------------------------- */
 int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, const int32_t *thr,
                            const uint64_t *flip, uint64_t *out,
-                           int64_t M, int64_t N, int64_t K, esp_stream stream);
+                           int64_t M, int64_t N, int64_t K, int engine, esp_stream stream);
 
 int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
                            const uint64_t *flip, uint64_t *out,
                            int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
-                           void *workspace, size_t workspace_bytes, esp_stream stream);
+                           void *workspace, size_t workspace_bytes, int engine, esp_stream stream);
+
+int esp_bconv_mfma(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                   int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                   void *workspace, size_t workspace_bytes, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
 /* Zero-padding correction (Sec. 5.2 "Zero-padding for convolutions"): the    */

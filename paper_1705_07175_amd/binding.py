@@ -18,6 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libespresso_hip.so")
 
 ESP_OK = 0
+ENGINE_XOR_POPCOUNT = 0
+ENGINE_MFMA = 1
 
 EXPORTS = (
     "esp_strerror", "esp_version", "esp_pack_f32", "esp_bgemm", "esp_unroll",
@@ -25,7 +27,7 @@ EXPORTS = (
     "esp_bmaxpool", "esp_dense_f32", "esp_conv_f32", "esp_bn_fold_f32", "esp_bn_sign_pack_f32",
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
-    "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma",
+    "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
 )
 
 _lib = None
@@ -64,8 +66,9 @@ def lib() -> ctypes.CDLL:
         l.esp_bn_sign_pack_f32.argtypes = [vp, vp, vp, vp, i64, i32, vp]
         l.esp_conv_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 9 + [vp]
         l.esp_bconv_needs_workspace.argtypes = [i32]
-        l.esp_bgemm_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
-        l.esp_bconv_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
+        l.esp_bgemm_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+        l.esp_bconv_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, i32, vp]
+        l.esp_bconv_mfma.argtypes = [vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
         l.esp_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
         l.esp_add_pad_correction.argtypes = [vp, vp] + [i32] * 8 + [vp]
         l.esp_bitplane_pack_u8.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -176,7 +179,8 @@ def bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad) -> int:
 
 
 def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
-          workspace: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+          workspace: torch.Tensor | None = None, out: torch.Tensor | None = None,
+          engine: int = ENGINE_XOR_POPCOUNT) -> torch.Tensor:
     """``esp_bconv``: packed NHWC x, packed filters [L2][kh][kw][Cw] -> int32 [B][H2][W2][L2]."""
     px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
     B, H, W, Cw = x.shape
@@ -189,9 +193,10 @@ def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     if out is None:
         out = torch.empty((B, max(H2, 0), max(W2, 0), L2), dtype=torch.int32, device=x.device)
-    _check(lib().esp_bconv(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
-                           _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
-           "esp_bconv")
+    fn = lib().esp_bconv_mfma if engine == ENGINE_MFMA else lib().esp_bconv
+    _check(fn(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
+              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
+           "esp_bconv_mfma" if engine == ENGINE_MFMA else "esp_bconv")
     return out
 
 
@@ -200,7 +205,7 @@ def bconv_needs_workspace(c: int) -> bool:
 
 
 def bgemm_bn_sign_pack(a: torch.Tensor, b: torch.Tensor, k: int, thr: torch.Tensor, flip: torch.Tensor,
-                       out: torch.Tensor | None = None) -> torch.Tensor:
+                       out: torch.Tensor | None = None, engine: int = ENGINE_XOR_POPCOUNT) -> torch.Tensor:
     """``esp_bgemm_bn_sign_pack``: product + folded threshold + sign -> packed [M][ceil(N/64)]."""
     pa, pb = _dev(a, PACKED, "a"), _dev(b, PACKED, "b")
     M, N = a.shape[0], b.shape[0]
@@ -211,14 +216,14 @@ def bgemm_bn_sign_pack(a: torch.Tensor, b: torch.Tensor, k: int, thr: torch.Tens
     if out is None:
         out = torch.empty((M, words(N)), dtype=PACKED, device=a.device)
     _check(lib().esp_bgemm_bn_sign_pack(pa, pb, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
-                                        _dev(out, PACKED, "out"), M, N, int(k), _stream()),
+                                        _dev(out, PACKED, "out"), M, N, int(k), int(engine), _stream()),
            "esp_bgemm_bn_sign_pack")
     return out
 
 
 def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.Tensor, flip: torch.Tensor,
                        stride: int, pad: int, workspace: torch.Tensor | None = None,
-                       out: torch.Tensor | None = None) -> torch.Tensor:
+                       out: torch.Tensor | None = None, engine: int = ENGINE_XOR_POPCOUNT) -> torch.Tensor:
     """``esp_bconv_bn_sign_pack``: convolution + folded threshold + sign -> packed NHWC bits."""
     px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
     B, H, W, Cw = x.shape
@@ -235,7 +240,7 @@ def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.T
     ws_len = workspace.numel() if workspace is not None else 0
     _check(lib().esp_bconv_bn_sign_pack(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
                                         _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
-                                        ws_ptr, ws_len, _stream()), "esp_bconv_bn_sign_pack")
+                                        ws_ptr, ws_len, int(engine), _stream()), "esp_bconv_bn_sign_pack")
     return out
 
 

@@ -504,11 +504,13 @@ int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, in
 }
 
 int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
-                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words, int engine,
                       hipStream_t stream)
 {
     if (M == 0)
         return ESP_OK;
+    if (engine == ESP_ENGINE_MFMA)
+        return bgemm_mfma_launch(A, B, nullptr, thr, flip, out, M, N, K_true, row_words, stream);
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29))
         return ESP_ESHAPE;
     TileOut o;
@@ -525,26 +527,18 @@ bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C)
 
 int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                           const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                          int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream)
+                          int kh, int kw, int stride, int pad, int H2, int W2, int engine,
+                          hipStream_t stream)
 {
     const int64_t M = (int64_t)B * H2 * W2;
     const int cdw = 2 * (C / 64);
     const int64_t row_dw = (int64_t)kh * kw * cdw;
     if (M >= (1ll << 31) || row_dw >= (1ll << 30) || (int64_t)B * H * W * cdw >= (1ll << 40))
         return ESP_ESHAPE;
-    ConvA a;
-    a.in = reinterpret_cast<const uint32_t *>(in);
-    a.rows = (int)M;
-    a.row_dw = (int)row_dw;
-    a.H = H;
-    a.W = W;
-    a.cdw = cdw;
-    a.stride = stride;
-    a.pad = pad;
-    a.d_w2 = make_fastdiv((uint32_t)W2);
-    a.d_h2 = make_fastdiv((uint32_t)H2);
-    a.d_cdw = make_fastdiv((uint32_t)cdw);
-    a.d_kw = make_fastdiv((uint32_t)kw);
+    if (engine == ESP_ENGINE_MFMA)
+        return bconv_mfma_launch(in, filt, C_out, thr, flip, bits_out, B, H, W, C, L2, kh, kw, stride, pad,
+                                 H2, W2, stream);
+    const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
     TileOut o;
     o.C = C_out;
     o.bits = bits_out;
@@ -575,10 +569,10 @@ extern "C" int esp_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C,
 
 extern "C" int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, const int32_t *thr,
                                       const uint64_t *flip, uint64_t *out,
-                                      int64_t M, int64_t N, int64_t K, esp_stream stream)
+                                      int64_t M, int64_t N, int64_t K, int engine, esp_stream stream)
 {
     using namespace esp;
-    if (M < 0 || N <= 0 || K <= 0)
+    if (M < 0 || N <= 0 || K <= 0 || (engine != ESP_ENGINE_XOR_POPCOUNT && engine != ESP_ENGINE_MFMA))
         return ESP_EINVAL;
     if (K >= kMaxK)
         return ESP_ESHAPE;
@@ -588,5 +582,5 @@ extern "C" int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, cons
         return ESP_EINVAL;
     if (!aligned(A, 8) || !aligned(B, 8) || !aligned(thr, 4) || !aligned(flip, 8) || !aligned(out, 8))
         return ESP_EALIGN;
-    return bgemm_bits_launch(A, B, thr, flip, out, M, N, K, ceil_div(K, 64), as_stream(stream));
+    return bgemm_bits_launch(A, B, thr, flip, out, M, N, K, ceil_div(K, 64), engine, as_stream(stream));
 }

@@ -284,6 +284,20 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
                                               stream);
 }
 
+int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                      const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
+                      int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream)
+{
+    const int64_t M = (int64_t)B * H2 * W2;
+    const int64_t K_true = (int64_t)kh * kw * C;
+    if (M >= (1ll << 31) || K_true >= kMaxMfmaK || (int64_t)B * H * W * (C / 32) >= (1ll << 40))
+        return ESP_ESHAPE;
+    const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
+    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64)};
+    return launch_mfma<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2, K_true, a.row_dw,
+                                    stream);
+}
+
 } // namespace esp
 
 extern "C" int esp_bgemm_mfma(const uint64_t *A, const uint64_t *B, int32_t *C,

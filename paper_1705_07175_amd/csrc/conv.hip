@@ -178,9 +178,10 @@ namespace esp {
 static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32, const int32_t *thr,
                      const uint64_t *flip, uint64_t *out_bits, int B, int H, int W, int C, int L2,
                      int kh, int kw, int stride, int pad, void *workspace, size_t workspace_bytes,
-                     hipStream_t stream)
+                     int engine, hipStream_t stream)
 {
-    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0)
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0 ||
+        (engine != ESP_ENGINE_XOR_POPCOUNT && engine != ESP_ENGINE_MFMA))
         return ESP_EINVAL;
     int64_t H2, W2;
     if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
@@ -197,7 +198,7 @@ static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32,
         return ESP_EALIGN;
     if (bconv_implicit_ok(in, filt, C))
         return bconv_implicit_launch(in, filt, out_i32, thr, flip, out_bits, B, H, W, C, L2, kh, kw,
-                                     stride, pad, (int)H2, (int)W2, stream);
+                                     stride, pad, (int)H2, (int)W2, engine, stream);
     // general channel counts: materialise the lowered matrix, then the plain product
     const size_t need = esp_bconv_workspace_bytes(B, H, W, C, kh, kw, stride, pad);
     if (!workspace || workspace_bytes < need)
@@ -211,7 +212,11 @@ static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32,
     const int64_t row_words = (int64_t)kh * kw * ceil_div(C, 64);
     const int64_t M = (int64_t)B * H2 * W2;
     if (out_bits)
-        return bgemm_bits_launch(lowered, filt, thr, flip, out_bits, M, L2, K_true, row_words, stream);
+        return bgemm_bits_launch(lowered, filt, thr, flip, out_bits, M, L2, K_true, row_words, engine,
+                                 stream);
+    if (engine == ESP_ENGINE_MFMA)
+        return bgemm_mfma_launch(lowered, filt, out_i32, nullptr, nullptr, nullptr, M, L2, K_true, row_words,
+                                 stream);
     return bgemm_launch(lowered, filt, out_i32, M, L2, K_true, row_words, stream);
 }
 
@@ -224,18 +229,29 @@ extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
     if (B > 0 && !out)
         return ESP_EINVAL;
     return esp::bconv_any(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw, stride, pad,
-                          workspace, workspace_bytes, esp::as_stream(stream));
+                          workspace, workspace_bytes, ESP_ENGINE_XOR_POPCOUNT, esp::as_stream(stream));
+}
+
+extern "C" int esp_bconv_mfma(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                              int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                              void *workspace, size_t workspace_bytes, esp_stream stream)
+{
+    if (B > 0 && !out)
+        return ESP_EINVAL;
+    return esp::bconv_any(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw, stride, pad,
+                          workspace, workspace_bytes, ESP_ENGINE_MFMA, esp::as_stream(stream));
 }
 
 extern "C" int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
                                       const uint64_t *flip, uint64_t *out,
                                       int B, int H, int W, int C, int L2, int kh, int kw, int stride,
-                                      int pad, void *workspace, size_t workspace_bytes, esp_stream stream)
+                                      int pad, void *workspace, size_t workspace_bytes, int engine,
+                                      esp_stream stream)
 {
     if (B > 0 && (!out || !thr || !flip))
         return ESP_EINVAL;
     return esp::bconv_any(in, filt, nullptr, thr, flip, out, B, H, W, C, L2, kh, kw, stride, pad,
-                          workspace, workspace_bytes, esp::as_stream(stream));
+                          workspace, workspace_bytes, engine, esp::as_stream(stream));
 }
 
 namespace esp {

@@ -75,10 +75,15 @@ int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, in
                  int64_t K_true, int64_t row_words, hipStream_t stream);
 
 // Same product with the folded batch-norm threshold + sign applied in the epilogue:
-// out [M][ceil(N/64)] packed bits instead of int32 dots.
+// out [M][ceil(N/64)] packed bits instead of int32 dots.  engine: esp_engine.
 int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
-                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                      uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words, int engine,
                       hipStream_t stream);
+
+// Matrix-core version of the product; exactly one of C (int32 dots) and bits (+ thr, flip).
+int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const int32_t *thr,
+                      const uint64_t *flip, uint64_t *bits, int64_t M, int64_t N, int64_t K_true,
+                      int64_t row_words, hipStream_t stream);
 
 // Convolution without a lowered matrix: the tile loader gathers the sliding volumes from
 // the packed NHWC input.  Usable when C is a multiple of 128 and the buffers are 16-byte
@@ -86,6 +91,10 @@ int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, 
 bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C);
 int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                           const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                          int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream);
+                          int kh, int kw, int stride, int pad, int H2, int W2, int engine,
+                          hipStream_t stream);
+int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                      const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
+                      int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream);
 
 } // namespace esp

@@ -93,6 +93,26 @@ struct ConvA {
     }
 };
 
+// Host side: describe the implicit lowered matrix of a convolution (C a multiple of 128).
+inline ConvA make_conv_a(const uint64_t *in, int B, int H, int W, int C, int kh, int kw, int stride,
+                         int pad, int H2, int W2)
+{
+    ConvA a;
+    a.in = reinterpret_cast<const uint32_t *>(in);
+    a.rows = B * H2 * W2;
+    a.cdw = 2 * (C / 64);
+    a.row_dw = kh * kw * a.cdw;
+    a.H = H;
+    a.W = W;
+    a.stride = stride;
+    a.pad = pad;
+    a.d_w2 = make_fastdiv((uint32_t)W2);
+    a.d_h2 = make_fastdiv((uint32_t)H2);
+    a.d_cdw = make_fastdiv((uint32_t)a.cdw);
+    a.d_kw = make_fastdiv((uint32_t)kw);
+    return a;
+}
+
 // Block id -> (tile row, tile column).  Consecutive block ids land on different XCDs, so
 // every XCD gets a contiguous range of tiles, walked in groups of kGroupM tile rows.
 // Returns false for the padding blocks beyond the last tile.

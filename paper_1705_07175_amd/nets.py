@@ -45,8 +45,9 @@ class BinaryMLP:
     """Sec. 6.2 network: float dense, then binary dense layers, BN + sign in between."""
 
     def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True,
-                 first_layer: str = "float"):
+                 first_layer: str = "float", engine: int = esp.ENGINE_XOR_POPCOUNT):
         self.batch = batch
+        self.engine = engine    # units that evaluate the fused binary layers (esp_engine)
         # "float": fp32 first layer on real-valued input; "bitplane": 8-bit input split into
         # bit-planes and run through the binary product (Sec. 4.3, Eq. 3), exact in integers
         self.first_layer = first_layer
@@ -90,7 +91,7 @@ class BinaryMLP:
             elif self.fused and self.batch > 8:
                 # threshold + sign + pack in the product's epilogue: no int32 round trip
                 esp.bgemm_bn_sign_pack(self.act[i - 1], self.wp[i], self.sizes[i], self.bn[i].thr,
-                                       self.bn[i].flip, out=self.act[i])
+                                       self.bn[i].flip, out=self.act[i], engine=self.engine)
             else:
                 esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
                 esp.bn_sign_pack(self.pre[i], self.bn[i].thr, self.bn[i].flip, out=self.act[i])
@@ -106,8 +107,10 @@ class BinaryCNN:
     """Sec. 6.3 network: float conv, binary 3x3 convs (border = -1), OR max-pools, binary dense."""
 
     def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda",
-                 keep_first_pre: bool = False, fused: bool = True, zero_pad: bool = False):
+                 keep_first_pre: bool = False, fused: bool = True, zero_pad: bool = False,
+                 engine: int = esp.ENGINE_XOR_POPCOUNT):
         self.batch = batch
+        self.engine = engine    # units that evaluate the fused binary layers (esp_engine)
         # zero_pad: add the load-time correction matrix (Sec. 5.2 "Zero-padding for
         # convolutions") after every binary convolution, i.e. true zero padding
         self.zero_pad = zero_pad
@@ -176,7 +179,7 @@ class BinaryCNN:
             elif kind == "conv":
                 if self.fused:
                     cur = esp.bconv_bn_sign_pack(cur, s["w"], s["c"], s["bn"].thr, s["bn"].flip, 1, 1,
-                                                 workspace=self.workspace, out=s["out"])
+                                                 workspace=self.workspace, out=s["out"], engine=self.engine)
                 else:
                     esp.bconv(cur, s["w"], s["c"], 1, 1, workspace=self.workspace, out=s["pre"])
                     if self.zero_pad:
@@ -187,7 +190,8 @@ class BinaryCNN:
                 if s["bn"] is None:
                     cur = esp.bgemm(a, s["w"], s["k"], out=s["pre"])
                 elif self.fused and self.batch > 8:
-                    cur = esp.bgemm_bn_sign_pack(a, s["w"], s["k"], s["bn"].thr, s["bn"].flip, out=s["out"])
+                    cur = esp.bgemm_bn_sign_pack(a, s["w"], s["k"], s["bn"].thr, s["bn"].flip, out=s["out"],
+                                                 engine=self.engine)
                 else:
                     esp.bgemm(a, s["w"], s["k"], out=s["pre"])
                     cur = esp.bn_sign_pack(s["pre"], s["bn"].thr, s["bn"].flip, out=s["out"])

@@ -78,11 +78,12 @@ def test_mlp_forward_bitplane_first_layer(batch):
     assert np.array_equal(scores, ref[3]["pre"])
 
 
-def test_mlp_batch1024_sampled_rows():
+@pytest.mark.parametrize("engine", [0, 1])
+def test_mlp_batch1024_sampled_rows(engine):
     # full-size batch on the GPU; the oracle recomputes a sample of the (independent) rows
     layers = synth.mlp_params()
     x = synth.mlp_input(1024)
-    net = nets.BinaryMLP(layers, 1024, EPS, DEV)
+    net = nets.BinaryMLP(layers, 1024, EPS, DEV, engine=engine)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     rows = np.array([0, 1, 63, 64, 511, 777, 1023])
     act0 = oracle.unpack_bits(esp.packed_to_numpy(net.act[0])[rows], 4096)
@@ -109,11 +110,12 @@ def _check_cnn(net, x, layers, rows, pad_value=-1):
     return ref[-1]["pre"]
 
 
-@pytest.mark.parametrize("batch,fused", [(1, False), (3, False), (1, True), (12, True)])
-def test_cnn_forward(batch, fused):
+@pytest.mark.parametrize("batch,fused,engine", [(1, False, 0), (3, False, 0), (1, True, 0), (12, True, 0),
+                                                (1, True, 1), (12, True, 1)])
+def test_cnn_forward(batch, fused, engine):
     layers = synth.cnn_params()
     x = synth.cnn_input(batch)
-    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True, fused=fused)
+    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True, fused=fused, engine=engine)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
     want = _check_cnn(net, x, layers, np.arange(batch))
@@ -130,10 +132,11 @@ def test_cnn_forward_zero_padding_correction():
     assert np.array_equal(scores, want)
 
 
-def test_cnn_batch256_sampled_images():
+@pytest.mark.parametrize("engine", [0, 1])
+def test_cnn_batch256_sampled_images(engine):
     layers = synth.cnn_params()
     x = synth.cnn_input(256)
-    net = nets.BinaryCNN(layers, 256, EPS, device=DEV, keep_first_pre=True)
+    net = nets.BinaryCNN(layers, 256, EPS, device=DEV, keep_first_pre=True, engine=engine)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     rows = np.array([0, 100, 255])
     want = _check_cnn(net, x, layers, rows)

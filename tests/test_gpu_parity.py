@@ -254,9 +254,10 @@ def test_bn_sign_pack(rows, C, K):
 
 
 # ------------------------------------------------------------------------------ fused epilogues
+@pytest.mark.parametrize("engine", [0, 1])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (9, 10, 4096), (64, 4096, 1024), (130, 70, 200), (257, 513, 1152),
                                    (1000, 128, 1152), (5, 1024, 8192), (1024, 1024, 1024)])
-def test_bgemm_bn_sign_pack(M, N, K):
+def test_bgemm_bn_sign_pack(M, N, K, engine):
     rng = np.random.default_rng(M * 31 + N * 17 + K)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
     bnp = synth.bn_params(rng, N)
@@ -264,13 +265,14 @@ def test_bgemm_bn_sign_pack(M, N, K):
     bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K)).astype(np.float32), bnp[3])
     thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
     got = esp.bgemm_bn_sign_pack(_packed_dev(a), _packed_dev(b), K, torch.from_numpy(thr).to(DEV),
-                                 esp.to_packed_tensor(flip, DEV))
+                                 esp.to_packed_tensor(flip, DEV), engine=engine)
     want = oracle.pack_bits(oracle.bn_sign(oracle.dense_pm1(a, b), bnp, synth.BN_EPS))
     assert got.shape == want.shape
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
-def test_bgemm_bn_sign_pack_large_tiles():
+@pytest.mark.parametrize("engine", [0, 1])
+def test_bgemm_bn_sign_pack_large_tiles(engine):
     M, N, K = 2900, 2950, 640
     rng = np.random.default_rng(77)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
@@ -278,7 +280,7 @@ def test_bgemm_bn_sign_pack_large_tiles():
     bnp = (bnp[0], bnp[1], (bnp[2] * 25).astype(np.float32), bnp[3])
     thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
     got = esp.bgemm_bn_sign_pack(_packed_dev(a), _packed_dev(b), K, torch.from_numpy(thr).to(DEV),
-                                 esp.to_packed_tensor(flip, DEV))
+                                 esp.to_packed_tensor(flip, DEV), engine=engine)
     want = oracle.pack_bits(oracle.bn_sign(oracle.dense_pm1(a, b), bnp, synth.BN_EPS))
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
@@ -291,8 +293,9 @@ FUSED_CONV_CASES = CONV_CASES + [
 ]
 
 
+@pytest.mark.parametrize("engine", [0, 1])
 @pytest.mark.parametrize("B,H,W,C,L2,kh,kw,stride,pad", FUSED_CONV_CASES)
-def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad):
+def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad, engine):
     rng = np.random.default_rng(B + 10 * H + 100 * C + kh + 1000 * L2 + 5)
     x = _pm1(rng, (B, H, W, C))
     f = _pm1(rng, (L2, kh, kw, C))
@@ -301,13 +304,13 @@ def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad):
     thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
     xp, fp = _packed_dev(x), _packed_dev(f)
     got = esp.bconv_bn_sign_pack(xp, fp, C, torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV),
-                                 stride, pad)
+                                 stride, pad, engine=engine)
     pre = oracle.conv_pm1(x, f, stride, pad, -1)
     want = oracle.pack_bits(oracle.bn_sign(pre, bnp, synth.BN_EPS))
     assert got.shape == want.shape
     assert np.array_equal(esp.packed_to_numpy(got), want)
     # the int32 route through the same loader
-    assert np.array_equal(esp.bconv(xp, fp, C, stride, pad).cpu().numpy(), pre)
+    assert np.array_equal(esp.bconv(xp, fp, C, stride, pad, engine=engine).cpu().numpy(), pre)
 
 
 # ------------------------------------------------------------------------------ zero-padding correction
