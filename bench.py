@@ -336,7 +336,8 @@ def _networks(torch, esp, nets, synth, dev, only=None):
         if only and only != ("bcnn", batch):
             continue
         x = torch.from_numpy(synth.cnn_input(batch)).to(dev)
-        for key, engine in ((str(batch), esp.ENGINE_XOR_POPCOUNT), (str(batch) + "_mfma_engine", esp.ENGINE_MFMA)):
+        for key, engine in ((str(batch), esp.ENGINE_XOR_POPCOUNT), (str(batch) + "_mfma_engine", esp.ENGINE_MFMA),
+                            (str(batch) + "_auto_engine", esp.ENGINE_AUTO)):
             net = nets.BinaryCNN(layers, batch, synth.BN_EPS, device=dev, engine=engine)
             res["bcnn"][key] = time_net(net, x, batch, 30)
             del net

@@ -62,7 +62,9 @@ enum esp_status {
 /* entry points that take an `engine` argument.  Results are identical.       */
 enum esp_engine {
     ESP_ENGINE_XOR_POPCOUNT = 0, /* vector ALU: v_xor + v_bcnt (the paper's XNOR/bit-count) */
-    ESP_ENGINE_MFMA = 1          /* matrix cores: bits expanded to 4-bit float operands      */
+    ESP_ENGINE_MFMA = 1,         /* matrix cores: bits expanded to 4-bit float operands      */
+    ESP_ENGINE_AUTO = 2          /* matrix cores when the product fills the chip with their  */
+                                 /* 256 x 128 tiles, the vector ALU's small tiles otherwise  */
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libespresso_hip.so")
 ESP_OK = 0
 ENGINE_XOR_POPCOUNT = 0
 ENGINE_MFMA = 1
+ENGINE_AUTO = 2
 
 EXPORTS = (
     "esp_strerror", "esp_version", "esp_pack_f32", "esp_bgemm", "esp_unroll",

@@ -509,7 +509,7 @@ int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, 
 {
     if (M == 0)
         return ESP_OK;
-    if (engine == ESP_ENGINE_MFMA)
+    if (resolve_engine(engine, M, N, K_true) == ESP_ENGINE_MFMA)
         return bgemm_mfma_launch(A, B, nullptr, thr, flip, out, M, N, K_true, row_words, stream);
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29))
         return ESP_ESHAPE;
@@ -535,7 +535,7 @@ int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_o
     const int64_t row_dw = (int64_t)kh * kw * cdw;
     if (M >= (1ll << 31) || row_dw >= (1ll << 30) || (int64_t)B * H * W * cdw >= (1ll << 40))
         return ESP_ESHAPE;
-    if (engine == ESP_ENGINE_MFMA)
+    if (resolve_engine(engine, M, L2, (int64_t)kh * kw * C) == ESP_ENGINE_MFMA)
         return bconv_mfma_launch(in, filt, C_out, thr, flip, bits_out, B, H, W, C, L2, kh, kw, stride, pad,
                                  H2, W2, stream);
     const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
@@ -572,7 +572,7 @@ extern "C" int esp_bgemm_bn_sign_pack(const uint64_t *A, const uint64_t *B, cons
                                       int64_t M, int64_t N, int64_t K, int engine, esp_stream stream)
 {
     using namespace esp;
-    if (M < 0 || N <= 0 || K <= 0 || (engine != ESP_ENGINE_XOR_POPCOUNT && engine != ESP_ENGINE_MFMA))
+    if (M < 0 || N <= 0 || K <= 0 || !engine_valid(engine))
         return ESP_EINVAL;
     if (K >= kMaxK)
         return ESP_ESHAPE;

@@ -180,8 +180,7 @@ static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32,
                      int kh, int kw, int stride, int pad, void *workspace, size_t workspace_bytes,
                      int engine, hipStream_t stream)
 {
-    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0 ||
-        (engine != ESP_ENGINE_XOR_POPCOUNT && engine != ESP_ENGINE_MFMA))
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0 || !engine_valid(engine))
         return ESP_EINVAL;
     int64_t H2, W2;
     if (!conv_shape_ok(B, H, W, C, kh, kw, stride, pad, &H2, &W2))
@@ -214,7 +213,7 @@ static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32,
     if (out_bits)
         return bgemm_bits_launch(lowered, filt, thr, flip, out_bits, M, L2, K_true, row_words, engine,
                                  stream);
-    if (engine == ESP_ENGINE_MFMA)
+    if (resolve_engine(engine, M, L2, K_true) == ESP_ENGINE_MFMA)
         return bgemm_mfma_launch(lowered, filt, out_i32, nullptr, nullptr, nullptr, M, L2, K_true, row_words,
                                  stream);
     return bgemm_launch(lowered, filt, out_i32, M, L2, K_true, row_words, stream);

@@ -59,7 +59,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bconv(p, p, p, 1, 4, 4, 64, 8, 3, 3, 1, 1, None, 0, None) == -4
     assert lib.esp_bconv_mfma(p, p, p, 1, 4, 4, 64, 8, 3, 3, 1, 1, None, 0, None) == -4
     assert lib.esp_bconv_bn_sign_pack(p, p, p, p, p, 1, 4, 4, 64, 8, 3, 3, 1, 1, p, 1 << 20, 7, None) == -1
-    assert lib.esp_bgemm_bn_sign_pack(p, p, p, p, p, 4, 4, 64, 2, None) == -1
+    assert lib.esp_bgemm_bn_sign_pack(p, p, p, p, p, 4, 4, 64, 3, None) == -1
     assert lib.esp_bconv(p, p, p, 1, 4, 4, 64, 8, 3, 3, 1, 1, p, 8, None) == -4
     assert lib.esp_bconv_workspace_bytes(2, 4, 4, 64, 3, 3, 1, 1) == 2 * 16 * 9 * 8
     assert lib.esp_bconv_workspace_bytes(2, 4, 4, 65, 3, 3, 1, 1) == 2 * 16 * 9 * 16

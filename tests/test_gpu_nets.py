@@ -111,7 +111,7 @@ def _check_cnn(net, x, layers, rows, pad_value=-1):
 
 
 @pytest.mark.parametrize("batch,fused,engine", [(1, False, 0), (3, False, 0), (1, True, 0), (12, True, 0),
-                                                (1, True, 1), (12, True, 1)])
+                                                (1, True, 1), (12, True, 1), (12, True, 2)])
 def test_cnn_forward(batch, fused, engine):
     layers = synth.cnn_params()
     x = synth.cnn_input(batch)
@@ -132,7 +132,7 @@ def test_cnn_forward_zero_padding_correction():
     assert np.array_equal(scores, want)
 
 
-@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("engine", [0, 1, 2])
 def test_cnn_batch256_sampled_images(engine):
     layers = synth.cnn_params()
     x = synth.cnn_input(256)
