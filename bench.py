@@ -183,7 +183,8 @@ def main() -> int:
 
 
 SUPPORTING = ("copy", "pack", "bn_sign_pack", "unroll", "bmaxpool", "bgemv", "bgemv_1g", "bconv_cfg2",
-              "bconv_conv2_b256", "bconv_conv6_b256")
+              "bconv_conv2_b256", "bconv_conv4_b256", "bconv_conv6_b256",
+              "bconv_conv2_b256_mfma", "bconv_conv4_b256_mfma", "bconv_conv6_b256_mfma")
 
 
 def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3):
@@ -278,9 +279,11 @@ def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3)
                     "ms": round(ms, 5), "bound": "alu", "achieved": round(tb, 2),
                     "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s", "frac": round(tb / VALU_PEAK_TBOPS, 4)})
     # the CNN's second and sixth layers at batch 256, fused threshold epilogue (bits out)
-    for name, h, c, l2 in (("bconv_conv2_b256", 32, 128, 128), ("bconv_conv6_b256", 8, 512, 512)):
-        if only != name:
+    for name, h, c, l2 in (("bconv_conv2_b256", 32, 128, 128), ("bconv_conv4_b256", 16, 256, 256),
+                           ("bconv_conv6_b256", 8, 512, 512)):
+        if only not in (name, name + "_mfma"):
             continue
+        engine = esp.ENGINE_MFMA if only.endswith("_mfma") else esp.ENGINE_XOR_POPCOUNT
         b = 256
         xin = rand_words((b, h, h, c // 64))
         filt = rand_words((l2, 3, 3, c // 64))
@@ -289,13 +292,14 @@ def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3)
         thr = torch.from_numpy(thr_np).to(dev)
         flip = esp.to_packed_tensor(flip_np, dev)
         bits = torch.empty((b, h, h, l2 // 64), dtype=esp.PACKED, device=dev)
-        ms, _ = _events_ms(lambda: esp.bconv_bn_sign_pack(xin, filt, c, thr, flip, 1, 1, out=bits),
+        ms, _ = _events_ms(lambda: esp.bconv_bn_sign_pack(xin, filt, c, thr, flip, 1, 1, out=bits, engine=engine),
                            steps, warmup, torch)
         bop = 2.0 * b * h * h * l2 * 9 * c
         tb = bop / (ms * 1e-3) / 1e12
-        out.append({"kernel": "bconv_bn_sign_pack (implicit GEMM)", "workload": name,
-                    "ms": round(ms, 5), "bound": "alu", "achieved": round(tb, 2),
-                    "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s", "frac": round(tb / VALU_PEAK_TBOPS, 4)})
+        peak = MFMA_FP4_PEAK_TOPS if engine == esp.ENGINE_MFMA else round(VALU_PEAK_TBOPS, 1)
+        out.append({"kernel": "bconv_bn_sign_pack (implicit GEMM)", "workload": only,
+                    "ms": round(ms, 5), "bound": "mfma" if engine == esp.ENGINE_MFMA else "alu",
+                    "achieved": round(tb, 2), "peak": peak, "unit": "Tbop/s", "frac": round(tb / peak, 4)})
     return out
 
 

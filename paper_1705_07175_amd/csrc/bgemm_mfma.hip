@@ -2,20 +2,18 @@
 // kernel for the dense contraction of Sec. 4.2, Eq. 2 of arXiv 1705.07175).
 //
 // gfx950's block-scaled MFMA takes 4-bit floating-point (E2M1) operands at twice the rate of
-// 8-bit ones.  A packed bit needs no real conversion to become such an operand:
-//   * A bits are used as {0, v}: masking a source dword with 0x11111111 << j leaves, in every
-//     nibble, either 0 or the E2M1 pattern 1, 2 or 4 = 0.5, 1.0 or 2.0; the instruction's
-//     per-block scale (2^1, 2^0, 2^-1) turns each of them into exactly 1.  One AND per
-//     operand dword (bit 3 of a nibble is the sign bit, so j = 3 takes a shift first).
-//   * B bits are used as +-1: the bit is moved to the nibble's sign position and combined
-//     with the magnitude pattern of 1.0 ((x & 0x88888888) ^ 0xAAAAAAAA: bit 1 -> +1.0,
-//     bit 0 -> -1.0).
-// Any permutation of k is allowed as long as both operands use the same one, so the four
-// masks j = 0..3 of one source dword simply feed four successive MFMA calls.
-// With a in {0,1} and b in {-1,+1} the accumulator holds r = sum_k a_k b_k exactly (fp32,
-// |r| <= K < 2^24) and the +-1 dot product is  2 r - sum_k b_k : a 0 bit of A (= -1, also the
-// -1 border of a convolution) contributes -b_k.  sum_k b_k = 2 popcount(B row) - K is
-// accumulated by the same lanes that unpack B, whose column is also their column of C.
+// 8-bit ones.  A packed bit needs no real conversion to become such an operand: masking a
+// source dword with 0x11111111 << j leaves, in every nibble, either 0 or the E2M1 pattern
+// 1, 2 or 4 = 0.5, 1.0 or 2.0, and the instruction's per-block scale (2^1, 2^0, 2^-1) turns
+// each of them into exactly 1.  That is one AND per operand dword (bit 3 of a nibble is the
+// sign bit, so j = 3 takes a shift first).  Any permutation of k is allowed as long as both
+// operands use the same one, so the four masks j = 0..3 of one source dword simply feed
+// four successive MFMA calls.
+// With a, b in {0,1} the accumulator holds c = sum_k a_k b_k exactly (fp32, c <= K < 2^24),
+// and the +-1 dot product follows from the row popcounts:
+//   dot = K - 2 * (pa + pb - 2 c) = K - 2 pa - 2 pb + 4 c.
+// A 0 bit is -1 throughout, which is also the -1 border of a convolution.  pa and pb are
+// counted once per block by the threads that fetch the packed rows from global memory.
 //
 // Tile: 256 threads = 2 x 2 waves, each wave 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32
 // (v_mfma_scale_f32_32x32x64_f8f6f4), fed from LDS slabs of packed rows in the same
@@ -36,7 +34,7 @@ constexpr int kMaxMfmaK = 1 << 24;             // fp32 accumulation stays exact
 constexpr int kScale2 = 128, kScale1 = 127, kScaleHalf = 126;
 
 template <int J>
-__device__ __forceinline__ v8i encode_a(const uint4 x)
+__device__ __forceinline__ v8i encode(const uint4 x)
 {
     v8i r;
     if (J < 3) {
@@ -56,29 +54,22 @@ __device__ __forceinline__ v8i encode_a(const uint4 x)
 }
 
 template <int J>
-__device__ __forceinline__ v8i encode_b(const uint4 x)
-{
-    v8i r;
-    r[0] = (int)(((x.x << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
-    r[1] = (int)(((x.y << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
-    r[2] = (int)(((x.z << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
-    r[3] = (int)(((x.w << (3 - J)) & 0x88888888u) ^ 0xAAAAAAAAu);
-    r[4] = r[5] = r[6] = r[7] = 0;
-    return r;
-}
-
-template <int J>
 __device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&xb)[2], v16f (&acc)[4][2])
 {
-    constexpr int sa = J == 0 ? kScale2 : (J == 1 ? kScale1 : kScaleHalf);
-    const v8i b0 = encode_b<J>(xb[0]);
-    const v8i b1 = encode_b<J>(xb[1]);
+    constexpr int sc = J == 0 ? kScale2 : (J == 1 ? kScale1 : kScaleHalf);
+    const v8i b0 = encode<J>(xb[0]);
+    const v8i b1 = encode<J>(xb[1]);
 #pragma unroll
     for (int f = 0; f < 4; ++f) {
-        const v8i a = encode_a<J>(xa[f]);
-        acc[f][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b0, acc[f][0], 4, 4, 0, sa, 0, kScale1);
-        acc[f][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b1, acc[f][1], 4, 4, 0, sa, 0, kScale1);
+        const v8i a = encode<J>(xa[f]);
+        acc[f][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b0, acc[f][0], 4, 4, 0, sc, 0, sc);
+        acc[f][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b1, acc[f][1], 4, 4, 0, sc, 0, sc);
     }
+}
+
+__device__ __forceinline__ int popc4(const uint4 v)
+{
+    return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
 }
 
 struct MfmaOut {
@@ -98,12 +89,17 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     constexpr int STAGE_DW = KG * 4;
     __shared__ uint4 As[KG][BM + 1];
     __shared__ uint4 Bs[KG][BN + 1];
+    __shared__ __align__(16) int pa_s[BM];   // set bits per A row of the tile
+    __shared__ int pb_s[BN];                 // set bits per B row (= output column)
 
     int tm, tn;
     if (!block_to_tile(tiles_m, tiles_n, tiles_per_xcd, &tm, &tn))
         return;
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x;
+    pa_s[tid] = 0;                           // BM == blockDim.x
+    if (tid < BN)
+        pb_s[tid] = 0;
     const int lane = tid % kWave;
     const int wave = tid / kWave;
     const int wm = (wave / 2) * 128;   // wave's row offset inside the block tile
@@ -124,6 +120,13 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         brow[i] = n < N ? B + (int64_t)n * row_dw : nullptr;
     }
     uint4 pa[A_CH], pb[B_CH];
+    int na[A_CH], nb[B_CH];   // set bits of the chunks this thread has fetched, per row
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+        na[i] = 0;
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+        nb[i] = 0;
     auto prefetch = [&](int stage) {
         const int kd = stage * STAGE_DW + kg_mine * 4;
         const typename ASrc::Step st = asrc.step(kd);
@@ -136,11 +139,15 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     };
     auto commit = [&]() {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i)
+        for (int i = 0; i < A_CH; ++i) {
             As[kg_mine][(tid + i * NT) / KG] = pa[i];
+            na[i] += popc4(pa[i]);
+        }
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i)
+        for (int i = 0; i < B_CH; ++i) {
             Bs[kg_mine][(tid + i * NT) / KG] = pb[i];
+            nb[i] += popc4(pb[i]);
+        }
     };
 
     v16f acc[4][2];
@@ -151,7 +158,6 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[f][g][r] = 0.0f;
-    int ones[2] = {0, 0};   // set bits of this lane's share of its two B columns
 
     // operand lane mapping of the 32x32x64 MFMA: row/column = lane % 32, k half = lane / 32
     const int lr = lane % 32, half = lane / 32;
@@ -170,10 +176,8 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             for (int f = 0; f < 4; ++f)
                 xa[f] = As[kg][wm + f * 32 + lr];
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
+            for (int g = 0; g < 2; ++g)
                 xb[g] = Bs[kg][wn + g * 32 + lr];
-                ones[g] += __popc(xb[g].x) + __popc(xb[g].y) + __popc(xb[g].z) + __popc(xb[g].w);
-            }
             mfma_group<0>(xa, xb, acc);
             mfma_group<1>(xa, xb, acc);
             mfma_group<2>(xa, xb, acc);
@@ -182,16 +186,22 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         __syncthreads();
     }
 
-    // sum_k b_k of the lane's two columns: both k halves together
-    int bsum[2];
+    // row popcounts: KG threads share a row, their partial counts meet in LDS
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
-        const int tot = ones[g] + __shfl_xor(ones[g], 32, kWave);
-        bsum[g] = 2 * tot - K_true;
-    }
+    for (int i = 0; i < A_CH; ++i)
+        atomicAdd(&pa_s[(tid + i * NT) / KG], na[i]);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+        atomicAdd(&pb_s[(tid + i * NT) / KG], nb[i]);
+    __syncthreads();
 
-    // result layout of a 32x32 block: lane -> column lane % 32; register r -> row
-    // 8 * (r / 4) + 4 * (lane / 32) + r % 4
+    // dot = K - 2 pa - 2 pb + 4 c.  Result layout of a 32x32 block: lane -> column lane % 32;
+    // register r -> row 8 * (r / 4) + 4 * (lane / 32) + r % 4.
+    int kb[2];   // K - 2 pb of the lane's two columns
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+        kb[g] = K_true - 2 * pb_s[wn + g * 32 + lr];
+
     if (BITS) {
         // one 64-column word per row of the wave tile: the comparison masks of the two
         // column blocks are its two halves (lanes 0-31: row R, lanes 32-63: row R + 4)
@@ -205,16 +215,22 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
         for (int f = 0; f < 4; ++f)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint64_t m0b = __ballot(2 * (int)acc[f][0][r] - bsum[0] >= lim[0]);
-                const uint64_t m1b = __ballot(2 * (int)acc[f][1][r] - bsum[1] >= lim[1]);
-                const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
-                const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
-                const int R = f * 32 + 8 * (r / 4) + r % 4;                          // compile-time
-                if (lane == R % 64)
-                    mine[R / 64] = w_lo;
-                if (lane == (R + 4) % 64)
-                    mine[(R + 4) / 64] = w_hi;
+            for (int q = 0; q < 4; ++q) {
+                const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[wm + f * 32 + 8 * q + 4 * half]);
+                const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int r = 4 * q + t;
+                    const uint64_t m0b = __ballot(4 * (int)acc[f][0][r] + kb[0] - 2 * pav[t] >= lim[0]);
+                    const uint64_t m1b = __ballot(4 * (int)acc[f][1][r] + kb[1] - 2 * pav[t] >= lim[1]);
+                    const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
+                    const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
+                    const int R = f * 32 + 8 * q + t;                                     // compile-time
+                    if (lane == R % 64)
+                        mine[R / 64] = w_lo;
+                    if (lane == (R + 4) % 64)
+                        mine[(R + 4) / 64] = w_hi;
+                }
             }
         const int w = (n0 + wn) >> 6;
         if (w < o.Nw) {
@@ -230,15 +246,21 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
         for (int f = 0; f < 4; ++f)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4;
-                if (row >= M)
-                    continue;
+            for (int q = 0; q < 4; ++q) {
+                const int rl = wm + f * 32 + 8 * q + 4 * half;
+                const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[rl]);
+                const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
 #pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    const int col = n0 + wn + g * 32 + lr;
-                    if (col < N)
-                        o.C[(int64_t)row * N + col] = 2 * (int)acc[f][g][r] - bsum[g];
+                for (int t = 0; t < 4; ++t) {
+                    const int row = m0 + rl + t;
+                    if (row >= M)
+                        continue;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int col = n0 + wn + g * 32 + lr;
+                        if (col < N)
+                            o.C[(int64_t)row * N + col] = 4 * (int)acc[f][g][4 * q + t] + kb[g] - 2 * pav[t];
+                    }
                 }
             }
     }
