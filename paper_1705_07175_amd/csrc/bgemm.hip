@@ -139,14 +139,15 @@ struct StoreSignBits {
         put(m0 + ty + TY * (tx & 7), M, (n0 >> 6) + (tx >> 3), lo, hi);
     }
 
-    // 4 x 4 counters per lane: one word per row i = 0..3
-    template <int TY>
-    __device__ __forceinline__ void tile(const int (&acc)[4][4], const int (&lim)[4], int m0, int n0,
+    // TM x 4 counters per lane (TM = 1, 2 or 4): one word per row i < TM
+    template <int TY, int TM>
+    __device__ __forceinline__ void tile(const int (&acc)[TM][4], const int (&lim)[4], int m0, int n0,
                                          int M, int tx, int ty) const
     {
+        static_assert(TM <= 4, "rows per lane");
         uint32_t x = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 x |= acc[i][c] <= lim[c] ? 0x10001u << (4 * i + c) : 0u;   // kept 16-bit periodic
@@ -160,7 +161,7 @@ struct StoreSignBits {
         hi |= lane_xor<4>(hi);
         lo |= lane_xor<8>(lo);
         hi |= lane_xor<8>(hi);
-        if (tx < 4)
+        if (tx < TM)
             put(m0 + ty + TY * tx, M, n0 >> 6, lo, hi);
     }
 };
@@ -276,7 +277,10 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
 #pragma unroll
         for (int j = 0; j < TN; ++j)
             lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
-        bits.template tile<TY>(acc, lim, m0, n0, M, tx, ty);
+        if constexpr (TM == 8)
+            bits.template tile<TY>(acc, lim, m0, n0, M, tx, ty);
+        else
+            bits.template tile<TY, TM>(acc, lim, m0, n0, M, tx, ty);
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -329,7 +333,11 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
     const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
     if (big_tiles >= 512)
         return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
-    return launch_tile2<64, 64, 4, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    // small products (dense layers at moderate batch, convolutions at batch 1): halve the
+    // rows per lane so that twice as many waves share the work when the chip is not full
+    if (ceil_div(M, 64) * ceil_div(N, 64) >= 256)
+        return launch_tile2<64, 64, 4, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    return launch_tile2<32, 64, 2, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
 }
 
 static int tile_matrix(const uint64_t *A, const uint64_t *B, const TileOut &o, int64_t M, int64_t N,
