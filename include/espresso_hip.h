@@ -195,6 +195,25 @@ int esp_bconv_mfma(const uint64_t *in, const uint64_t *filt, int32_t *out,
                    void *workspace, size_t workspace_bytes, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
+/* bconv_bn_sign_pack_pool2: esp_bconv_bn_sign_pack followed by the 2x2,      */
+/* stride-2 esp_bmaxpool, in one kernel.  In the network of Sec. 6.3 pooling  */
+/* acts on the +-1 activations, where the maximum is the OR of the sign bits; */
+/* a block tile that holds whole pairs of image rows ORs them before storing, */
+/* so the unpooled activations never reach memory.                            */
+/*   out uint64 [B][H2/2][W2/2][ceil(L2/64)]; other arguments as above; no    */
+/*   workspace.  Only for shapes where esp_bconv_pool2_fusable returns 1:     */
+/*   C a multiple of 128, H2 even, W2 a power of two in [2, 64]; otherwise    */
+/*   ESP_ESHAPE (ESP_EALIGN if in / filt are not 16-byte aligned) and the     */
+/*   caller chains the two separate calls.  Results are identical to them.    */
+/* ------------------------------------------------------------------------- */
+int esp_bconv_pool2_fusable(int H, int W, int C, int kh, int kw, int stride, int pad);
+
+int esp_bconv_bn_sign_pack_pool2(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
+                                 const uint64_t *flip, uint64_t *out,
+                                 int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                                 int engine, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
 /* Zero-padding correction (Sec. 5.2 "Zero-padding for convolutions"): the    */
 /* binary convolution above treats the border as -1; a zero-padded ("same")   */
 /* convolution is obtained by adding a correction matrix that depends only on */

@@ -29,6 +29,7 @@ EXPORTS = (
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
+    "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2",
 )
 
 _lib = None
@@ -76,7 +77,13 @@ def lib() -> ctypes.CDLL:
         l.esp_row_sums.argtypes = [vp, vp, i64, i64, i64, vp]
         l.esp_bitplane_combine.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         l.esp_bgemm_mfma.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        l.esp_bconv_pool2_fusable.argtypes = [i32] * 7
+        l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
+        l.esp_version.argtypes = []
         for name in EXPORTS:
+            # without a prototype ctypes would pass pointers as 32-bit ints: refuse to load
+            if getattr(l, name).argtypes is None:
+                raise ImportError("binding.py declares no argument types for %s" % name)
             if name not in ("esp_strerror", "esp_bconv_workspace_bytes"):
                 getattr(l, name).restype = i32
         _lib = l
@@ -242,6 +249,31 @@ def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.T
     _check(lib().esp_bconv_bn_sign_pack(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
                                         _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
                                         ws_ptr, ws_len, int(engine), _stream()), "esp_bconv_bn_sign_pack")
+    return out
+
+
+def bconv_pool2_fusable(h: int, w: int, c: int, kh: int, kw: int, stride: int, pad: int) -> bool:
+    """``esp_bconv_pool2_fusable``: can the 2x2 max-pool be fused behind this convolution?"""
+    return bool(lib().esp_bconv_pool2_fusable(int(h), int(w), int(c), int(kh), int(kw), int(stride), int(pad)))
+
+
+def bconv_bn_sign_pack_pool2(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.Tensor,
+                             flip: torch.Tensor, stride: int, pad: int, out: torch.Tensor | None = None,
+                             engine: int = ENGINE_XOR_POPCOUNT) -> torch.Tensor:
+    """``esp_bconv_bn_sign_pack_pool2``: convolution + threshold + sign + 2x2 OR max-pool."""
+    px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
+    B, H, W, Cw = x.shape
+    L2, kh, kw, Cw2 = filt.shape
+    if Cw != words(c) or Cw2 != Cw or thr.numel() != L2 or flip.numel() != words(L2):
+        raise ValueError("shape mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if out is None:
+        out = torch.empty((B, max(H2, 0) // 2, max(W2, 0) // 2, words(L2)), dtype=PACKED, device=x.device)
+    elif out.numel() != B * (H2 // 2) * (W2 // 2) * words(L2):
+        raise ValueError("out has the wrong size")
+    _check(lib().esp_bconv_bn_sign_pack_pool2(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
+                                              _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride,
+                                              pad, int(engine), _stream()), "esp_bconv_bn_sign_pack_pool2")
     return out
 
 

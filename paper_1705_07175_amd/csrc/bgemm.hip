@@ -89,11 +89,18 @@ __device__ __forceinline__ uint32_t nibble_swap(uint32_t own, bool lane_bit)
 // Instead of reducing every word over the 16 lanes, the nibbles are transposed across the
 // lanes (4 butterfly steps on two registers), after which lane tx holds one complete word.
 // Requires TX == 16 and a tile origin n0 that is a multiple of 64; all 64 lanes must call.
+struct LaneWord {
+    int rl, wl;             // row and 64-column word inside the block tile
+    bool have;              // this lane holds a word
+    uint32_t lo, hi;
+};
+
 struct StoreSignBits {
-    uint64_t *out;          // [M][Nw]
+    uint64_t *out;          // [M][Nw], or [M/4][Nw] behind a fused 2x2 max-pool
     const int32_t *thr;     // [N]
     const uint64_t *flip;   // [Nw]
     int Nw;
+    int pool_log2w;         // 0: no pooling; else log2 of the output width W2 of the convolution
 
     // mismatch-count threshold: dot = K - 2a >= thr  <=>  a <= floor((K - thr) / 2)
     __device__ __forceinline__ int mismatch_limit(int col, int N, int K_true) const
@@ -104,16 +111,15 @@ struct StoreSignBits {
         return (K_true - t) >> 1;
     }
 
-    __device__ __forceinline__ void put(int r, int M, int w, uint32_t lo, uint32_t hi) const
+    // final bits of a lane's word (0 beyond the last word of the row)
+    __device__ __forceinline__ uint64_t finish(const LaneWord &lw, int w) const
     {
-        if (r < M && w < Nw)
-            out[(int64_t)r * Nw + w] = (((uint64_t)hi << 32) | lo) ^ flip[w];
+        return (lw.have && w < Nw) ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flip[w]) : 0ull;
     }
 
     // 8 x 8 counters per lane: slots q = jg*8 + i, lo register = word jg 0, hi = word jg 1
     template <int TY>
-    __device__ __forceinline__ void tile(const int (&acc)[8][8], const int (&lim)[8], int m0, int n0,
-                                         int M, int tx, int ty) const
+    __device__ __forceinline__ LaneWord tile(const int (&acc)[8][8], const int (&lim)[8], int tx, int ty) const
     {
         uint32_t lo = 0, hi = 0;
 #pragma unroll
@@ -136,13 +142,12 @@ struct StoreSignBits {
         lo = up ? got : lo;
         hi = up ? hi : got;
         // lane tx now holds the word of slot q = tx: row ty + TY*(tx % 8), word tx / 8
-        put(m0 + ty + TY * (tx & 7), M, (n0 >> 6) + (tx >> 3), lo, hi);
+        return LaneWord{ty + TY * (tx & 7), tx >> 3, true, lo, hi};
     }
 
     // TM x 4 counters per lane (TM = 1, 2 or 4): one word per row i < TM
     template <int TY, int TM>
-    __device__ __forceinline__ void tile(const int (&acc)[TM][4], const int (&lim)[4], int m0, int n0,
-                                         int M, int tx, int ty) const
+    __device__ __forceinline__ LaneWord tile(const int (&acc)[TM][4], const int (&lim)[4], int tx, int ty) const
     {
         static_assert(TM <= 4, "rows per lane");
         uint32_t x = 0;
@@ -161,8 +166,7 @@ struct StoreSignBits {
         hi |= lane_xor<4>(hi);
         lo |= lane_xor<8>(lo);
         hi |= lane_xor<8>(hi);
-        if (tx < TM)
-            put(m0 + ty + TY * tx, M, n0 >> 6, lo, hi);
+        return LaneWord{ty + TY * tx, 0, tx < TM, lo, hi};
     }
 };
 
@@ -277,10 +281,26 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
 #pragma unroll
         for (int j = 0; j < TN; ++j)
             lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+        LaneWord lw;
         if constexpr (TM == 8)
-            bits.template tile<TY>(acc, lim, m0, n0, M, tx, ty);
+            lw = bits.template tile<TY>(acc, lim, tx, ty);
         else
-            bits.template tile<TY, TM>(acc, lim, m0, n0, M, tx, ty);
+            lw = bits.template tile<TY, TM>(acc, lim, tx, ty);
+        const int w = (n0 >> 6) + lw.wl;
+        const uint64_t word = bits.finish(lw, w);
+        if (bits.pool_log2w == 0) {
+            if (lw.have && m0 + lw.rl < M && w < bits.Nw)
+                bits.out[(int64_t)(m0 + lw.rl) * bits.Nw + w] = word;
+        } else {
+            // 2x2 max-pool of +-1 values = OR of the sign bits: the tile's words meet in LDS
+            // (the A slab is free after the last stage) and every pooled word ORs its four sources
+            constexpr int WPT = BN / 64;
+            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0]);
+            if (lw.have)
+                wt[lw.rl * WPT + lw.wl] = word;
+            __syncthreads();
+            pool_tile_store<BM, WPT, NT>(wt, bits.out, m0, n0, M, bits.Nw, bits.pool_log2w, tid);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -297,6 +317,7 @@ struct TileOut {
     uint64_t *bits = nullptr;        // packed signs [M][ceil(N/64)] (BITS == true)
     const int32_t *thr = nullptr;
     const uint64_t *flip = nullptr;
+    int pool_log2w = 0;              // fused 2x2 max-pool behind the sign: log2 of the conv's W2
 };
 
 template <int BM, int BN, int TM, int TN, class ASrc, bool VEC16B>
@@ -312,7 +333,7 @@ static int launch_tile2(const ASrc &asrc, const uint32_t *b, const TileOut &o, i
     const dim3 grid((unsigned)(per_xcd * kXcd));
     const dim3 block((BM / TM) * (BN / TN));
     const StoreDots dots{o.C, (N % 4 == 0) && aligned(o.C, 16)};
-    const StoreSignBits bits{o.bits, o.thr, o.flip, (int)ceil_div(N, 64)};
+    const StoreSignBits bits{o.bits, o.thr, o.flip, (int)ceil_div(N, 64), o.pool_log2w};
     if (o.bits)
         hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, ASrc, VEC16B, true>), grid, block, 0, stream,
                            asrc, b, dots, bits, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
@@ -330,12 +351,14 @@ template <class ASrc, bool VEC16B>
 static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
                        int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
+    // a fused 2x2 pool needs whole pairs of image rows in a tile: BM a multiple of 2 * W2
+    const int quantum = o.pool_log2w ? 2 << o.pool_log2w : 1;
     const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
-    if (big_tiles >= 512)
+    if (big_tiles >= 512 || quantum > 64)
         return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     // small products (dense layers at moderate batch, convolutions at batch 1): halve the
     // rows per lane so that twice as many waves share the work when the chip is not full
-    if (ceil_div(M, 64) * ceil_div(N, 64) >= 256)
+    if (ceil_div(M, 64) * ceil_div(N, 64) >= 256 || quantum > 32)
         return launch_tile2<64, 64, 4, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     return launch_tile2<32, 64, 2, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
 }
@@ -535,7 +558,7 @@ bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C)
 
 int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                           const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                          int kh, int kw, int stride, int pad, int H2, int W2, int engine,
+                          int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w, int engine,
                           hipStream_t stream)
 {
     const int64_t M = (int64_t)B * H2 * W2;
@@ -545,13 +568,14 @@ int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_o
         return ESP_ESHAPE;
     if (resolve_engine(engine, M, L2, (int64_t)kh * kw * C) == ESP_ENGINE_MFMA)
         return bconv_mfma_launch(in, filt, C_out, thr, flip, bits_out, B, H, W, C, L2, kh, kw, stride, pad,
-                                 H2, W2, stream);
+                                 H2, W2, pool_log2w, stream);
     const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
     TileOut o;
     o.C = C_out;
     o.bits = bits_out;
     o.thr = thr;
     o.flip = flip;
+    o.pool_log2w = pool_log2w;
     return launch_tile<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2,
                                     (int64_t)kh * kw * C, row_dw, stream);
 }

@@ -78,6 +78,8 @@ struct MfmaOut {
     const int32_t *thr;
     const uint64_t *flip;
     int Nw;
+    int pool_log2w;         // 0: no pooling; else bits is [M/4][Nw] behind a fused 2x2 max-pool
+                            // and this is log2 of the convolution's output width W2
 };
 
 template <class ASrc, bool VEC16B, bool BITS>
@@ -233,14 +235,25 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
                 }
             }
         const int w = (n0 + wn) >> 6;
-        if (w < o.Nw) {
-            const uint64_t fl = o.flip[w];
+        const uint64_t fl = w < o.Nw ? o.flip[w] : 0ull;
+        if (o.pool_log2w == 0) {
+            if (w < o.Nw) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int row = m0 + wm + h * 64 + lane;
-                if (row < M)
-                    o.bits[(int64_t)row * o.Nw + w] = mine[h] ^ fl;
+                for (int h = 0; h < 2; ++h) {
+                    const int row = m0 + wm + h * 64 + lane;
+                    if (row < M)
+                        o.bits[(int64_t)row * o.Nw + w] = mine[h] ^ fl;
+                }
             }
+        } else {
+            // OR max-pool: the tile's words meet in LDS (the A slab is free by now)
+            constexpr int WPT = BN / 64;
+            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                wt[(wm + h * 64 + lane) * WPT + (wn >> 6)] = mine[h] ^ fl;
+            __syncthreads();
+            pool_tile_store<BM, WPT, NT>(wt, o.bits, m0, n0, M, o.Nw, o.pool_log2w, tid);
         }
     } else {
 #pragma unroll
@@ -294,7 +307,7 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
         return ESP_OK;
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29) || K_true >= kMaxMfmaK)
         return ESP_ESHAPE;
-    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64)};
+    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64), 0};
     const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
     const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
@@ -308,14 +321,14 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
 
 int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                       const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                      int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream)
+                      int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w, hipStream_t stream)
 {
     const int64_t M = (int64_t)B * H2 * W2;
     const int64_t K_true = (int64_t)kh * kw * C;
     if (M >= (1ll << 31) || K_true >= kMaxMfmaK || (int64_t)B * H * W * (C / 32) >= (1ll << 40))
         return ESP_ESHAPE;
     const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
-    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64)};
+    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64), pool_log2w};
     return launch_mfma<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2, K_true, a.row_dw,
                                     stream);
 }

@@ -174,11 +174,23 @@ extern "C" int esp_bconv_needs_workspace(int C) { return C % 128 != 0; }
 
 namespace esp {
 
+// log2 of W2 if a 2x2 / stride-2 max-pool can be fused behind this convolution, else 0:
+// the implicit (C % 128 == 0) path only, whole pairs of image rows in every block tile.
+static int pool2_log2w(int C, int64_t H2, int64_t W2)
+{
+    if (C % 128 != 0 || H2 < 2 || H2 % 2 != 0 || W2 < 2 || W2 > 64 || (W2 & (W2 - 1)) != 0)
+        return 0;
+    int l = 0;
+    while ((1ll << l) < W2)
+        ++l;
+    return l;
+}
+
 // Shared by esp_bconv and esp_bconv_bn_sign_pack: exactly one of out_i32 / out_bits is set.
 static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32, const int32_t *thr,
                      const uint64_t *flip, uint64_t *out_bits, int B, int H, int W, int C, int L2,
                      int kh, int kw, int stride, int pad, void *workspace, size_t workspace_bytes,
-                     int engine, hipStream_t stream)
+                     int engine, hipStream_t stream, bool pool2 = false)
 {
     if (B < 0 || H <= 0 || W <= 0 || C <= 0 || L2 <= 0 || kh <= 0 || kw <= 0 || !engine_valid(engine))
         return ESP_EINVAL;
@@ -195,9 +207,17 @@ static int bconv_any(const uint64_t *in, const uint64_t *filt, int32_t *out_i32,
     if (!aligned(in, 8) || !aligned(filt, 8) || !aligned(out_i32, 4) || !aligned(out_bits, 8) ||
         !aligned(thr, 4) || !aligned(flip, 8))
         return ESP_EALIGN;
+    int pool_log2w = 0;
+    if (pool2) {
+        pool_log2w = pool2_log2w(C, H2, W2);
+        if (pool_log2w == 0)
+            return ESP_ESHAPE;
+        if (!bconv_implicit_ok(in, filt, C))
+            return ESP_EALIGN;
+    }
     if (bconv_implicit_ok(in, filt, C))
         return bconv_implicit_launch(in, filt, out_i32, thr, flip, out_bits, B, H, W, C, L2, kh, kw,
-                                     stride, pad, (int)H2, (int)W2, engine, stream);
+                                     stride, pad, (int)H2, (int)W2, pool_log2w, engine, stream);
     // general channel counts: materialise the lowered matrix, then the plain product
     const size_t need = esp_bconv_workspace_bytes(B, H, W, C, kh, kw, stride, pad);
     if (!workspace || workspace_bytes < need)
@@ -251,6 +271,28 @@ extern "C" int esp_bconv_bn_sign_pack(const uint64_t *in, const uint64_t *filt, 
         return ESP_EINVAL;
     return esp::bconv_any(in, filt, nullptr, thr, flip, out, B, H, W, C, L2, kh, kw, stride, pad,
                           workspace, workspace_bytes, engine, esp::as_stream(stream));
+}
+
+extern "C" int esp_bconv_pool2_fusable(int H, int W, int C, int kh, int kw, int stride, int pad)
+{
+    using namespace esp;
+    if (H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0)
+        return 0;
+    int64_t H2, W2;
+    if (!conv_shape_ok(1, H, W, C, kh, kw, stride, pad, &H2, &W2))
+        return 0;
+    return pool2_log2w(C, H2, W2) != 0;
+}
+
+extern "C" int esp_bconv_bn_sign_pack_pool2(const uint64_t *in, const uint64_t *filt, const int32_t *thr,
+                                            const uint64_t *flip, uint64_t *out,
+                                            int B, int H, int W, int C, int L2, int kh, int kw, int stride,
+                                            int pad, int engine, esp_stream stream)
+{
+    if (B > 0 && (!out || !thr || !flip))
+        return ESP_EINVAL;
+    return esp::bconv_any(in, filt, nullptr, thr, flip, out, B, H, W, C, L2, kh, kw, stride, pad, nullptr, 0,
+                          engine, esp::as_stream(stream), true);
 }
 
 namespace esp {

@@ -100,13 +100,17 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
 // Convolution without a lowered matrix: the tile loader gathers the sliding volumes from
 // the packed NHWC input.  Usable when C is a multiple of 128 and the buffers are 16-byte
 // aligned.  Exactly one of C_out (int32 [B][H2][W2][L2]) and bits_out (+ thr, flip) is set.
+// pool_log2w != 0 (bits_out only): a 2x2 / stride-2 max-pool is applied to the sign bits in
+// the epilogue and bits_out is [B][H2/2][W2/2][ceil(L2/64)]; needs H2 even and
+// W2 == 1 << pool_log2w with 2 <= W2 <= 64.
 bool bconv_implicit_ok(const uint64_t *in, const uint64_t *filt, int C);
 int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                           const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                          int kh, int kw, int stride, int pad, int H2, int W2, int engine,
+                          int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w, int engine,
                           hipStream_t stream);
 int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                       const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
-                      int kh, int kw, int stride, int pad, int H2, int W2, hipStream_t stream);
+                      int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w,
+                      hipStream_t stream);
 
 } // namespace esp

@@ -131,4 +131,28 @@ __device__ __forceinline__ bool block_to_tile(int tiles_m, int tiles_n, int tile
     return true;
 }
 
+// Fused 2x2 / stride-2 max-pool behind the sign (Sec. 6.3: pooling acts on +-1 activations,
+// so the maximum is the OR of the sign bits).  wt holds the BM x WPT packed words of a block
+// tile whose BM rows are whole pairs of image rows (BM a multiple of 2 * W2, W2 = 1 << log2w,
+// tile origin m0 a multiple of BM): pooled row m0/4 + pp ORs local rows
+// 2*pl*W2 + 2*pn + {0, 1, W2, W2 + 1} with pl = pp / (W2/2), pn = pp % (W2/2).
+// M is a multiple of 2 * W2, so a pooled row is valid exactly when it is below M / 4.
+template <int BM, int WPT, int NT>
+__device__ __forceinline__ void pool_tile_store(const uint64_t *wt, uint64_t *__restrict__ out, int m0,
+                                                int n0, int M, int Nw, int log2w, int tid)
+{
+    const int W2 = 1 << log2w;
+    for (int t = tid; t < (BM / 4) * WPT; t += NT) {
+        const int wl = t % WPT, pp = t / WPT;
+        const int pl = pp >> (log2w - 1), pn = pp & ((W2 >> 1) - 1);
+        const int base = ((2 * pl) << log2w) + 2 * pn;
+        const uint64_t v = wt[base * WPT + wl] | wt[(base + 1) * WPT + wl] | wt[(base + W2) * WPT + wl] |
+                           wt[(base + W2 + 1) * WPT + wl];
+        const int prow = (m0 >> 2) + pp;
+        const int w = (n0 >> 6) + wl;
+        if (prow < (M >> 2) && w < Nw)
+            out[(int64_t)prow * Nw + w] = v;
+    }
+}
+
 } // namespace esp

@@ -108,7 +108,7 @@ class BinaryCNN:
 
     def __init__(self, layers, batch: int, eps: float, hw: int = 32, device="cuda",
                  keep_first_pre: bool = False, fused: bool = True, zero_pad: bool = False,
-                 engine: int = esp.ENGINE_XOR_POPCOUNT):
+                 engine: int = esp.ENGINE_XOR_POPCOUNT, fuse_pool: bool = True):
         self.batch = batch
         self.engine = engine    # units that evaluate the fused binary layers (esp_engine)
         # zero_pad: add the load-time correction matrix (Sec. 5.2 "Zero-padding for
@@ -118,6 +118,7 @@ class BinaryCNN:
             fused = False
         self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
         self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
+        self.fuse_pool = fuse_pool and fused   # OR max-pool inside the preceding convolution's epilogue
         self.steps = []          # one record per layer, in order
         h = hw
         c = layers[0]["w"].shape[3]
@@ -128,6 +129,11 @@ class BinaryCNN:
             rec = {"kind": kind}
             if kind == "pool":
                 rec.update(c=c, h=h)
+                prev = self.steps[-1]
+                # a binary convolution right before the pool takes it into its own epilogue
+                rec["fused_into_conv"] = bool(self.fuse_pool and i > 1 and prev["kind"] == "conv" and
+                                              esp.bconv_pool2_fusable(h, h, prev["c"], 3, 3, 1, 1))
+                prev["pool_after"] = rec["fused_into_conv"]
                 h //= 2
                 rec["out"] = torch.empty((batch, h, h, esp.words(c)), dtype=esp.PACKED, device=device)
             elif kind == "conv":
@@ -168,7 +174,8 @@ class BinaryCNN:
         for i, s in enumerate(self.steps):
             kind = s["kind"]
             if kind == "pool":
-                cur = esp.bmaxpool(cur, s["c"], 2, 2, out=s["out"])
+                if not s["fused_into_conv"]:
+                    cur = esp.bmaxpool(cur, s["c"], 2, 2, out=s["out"])
             elif kind == "conv" and i == 0:
                 if first_act is None:
                     esp.conv_f32_bn_sign_pack(x, s["w"], s["bn"].thr, s["bn"].sgn, 1, 1, out=s["out"],
@@ -177,7 +184,10 @@ class BinaryCNN:
                     s["out"].copy_(first_act)
                 cur = s["out"]
             elif kind == "conv":
-                if self.fused:
+                if self.fused and s.get("pool_after"):
+                    cur = esp.bconv_bn_sign_pack_pool2(cur, s["w"], s["c"], s["bn"].thr, s["bn"].flip, 1, 1,
+                                                       out=self.steps[i + 1]["out"], engine=self.engine)
+                elif self.fused:
                     cur = esp.bconv_bn_sign_pack(cur, s["w"], s["c"], s["bn"].thr, s["bn"].flip, 1, 1,
                                                  workspace=self.workspace, out=s["out"], engine=self.engine)
                 else:

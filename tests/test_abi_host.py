@@ -35,6 +35,28 @@ def test_library_exports_every_declared_symbol():
     assert "unknown" in esp.strerror(-99)
 
 
+def test_binding_prototypes_match_the_header():
+    # every declared function has ctypes argument types of the declared arity and pointer-ness
+    # (a missing prototype would pass 64-bit device pointers as 32-bit ints)
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    lib = esp.lib()
+    seen = 0
+    for m in re.finditer(r"\b(esp_[a-z0-9_]+)\s*\(([^)]*)\)\s*;", text):
+        name, params = m.group(1), m.group(2).strip()
+        plist = [] if params in ("", "void") else [q.strip() for q in params.split(",")]
+        argtypes = getattr(lib, name).argtypes
+        assert argtypes is not None and len(argtypes) == len(plist), name
+        for decl, at in zip(plist, argtypes):
+            is_ptr = "*" in decl or decl.startswith("esp_stream")
+            assert is_ptr == (at in (ctypes.c_void_p, ctypes.c_char_p)), (name, decl, at)
+            if "int64_t" in decl and not is_ptr:
+                assert at is ctypes.c_int64, (name, decl)
+            if "size_t" in decl and not is_ptr:
+                assert at is ctypes.c_size_t, (name, decl)
+        seen += 1
+    assert seen == len(esp.EXPORTS)
+
+
 def test_argument_errors_are_reported_without_a_gpu():
     lib = esp.lib()
     buf = (ctypes.c_uint64 * 64)()
@@ -83,6 +105,20 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bitplane_combine(p, p, None, 2, 1, 4, None) == -1
     assert lib.esp_conv_f32_bn_sign_pack(p, p, p, p, None, None, 1, 4, 4, 3, 8, 3, 3, 1, 1, None) == -1
     assert lib.esp_bn_fold(None, p, p, p, 1e-4, 4, p, p) == -1
+    # fused pool: shapes that cannot hold whole row pairs in a tile are refused up front
+    assert lib.esp_bconv_pool2_fusable(32, 32, 128, 3, 3, 1, 1) == 1
+    assert lib.esp_bconv_pool2_fusable(8, 8, 512, 3, 3, 1, 1) == 1
+    assert lib.esp_bconv_pool2_fusable(32, 32, 64, 3, 3, 1, 1) == 0
+    assert lib.esp_bconv_pool2_fusable(7, 8, 128, 3, 3, 1, 1) == 0
+    assert lib.esp_bconv_pool2_fusable(8, 12, 128, 3, 3, 1, 1) == 0
+    assert lib.esp_bconv_pool2_fusable(8, 128, 128, 3, 3, 1, 1) == 0
+    assert lib.esp_bconv_pool2_fusable(8, 8, 128, 3, 3, 0, 1) == 0
+    assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, None, 1, 8, 8, 128, 8, 3, 3, 1, 1, 0, None) == -1
+    assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, p, 1, 8, 8, 128, 8, 3, 3, 1, 1, 5, None) == -1
+    assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, p, 1, 8, 8, 64, 8, 3, 3, 1, 1, 0, None) == -3
+    assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, p, 1, 7, 8, 128, 8, 3, 3, 1, 1, 0, None) == -3
+    assert lib.esp_bconv_bn_sign_pack_pool2(p + 8, p, p, p, p, 1, 8, 8, 128, 8, 3, 3, 1, 1, 0, None) == -2
+    assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, p, 0, 8, 8, 128, 8, 3, 3, 1, 1, 0, None) == 0
 
 
 def _check_fold(gamma, beta, mean, var, eps, lo, hi):

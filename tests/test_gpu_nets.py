@@ -105,17 +105,23 @@ def _check_cnn(net, x, layers, rows, pad_value=-1):
             continue
         if "pre" in r and (not net.fused or s.get("bn") is None):
             assert np.array_equal(s["pre"].cpu().numpy()[rows], r["pre"]), i
+        if s.get("pool_after"):
+            continue    # pool fused into this convolution: only the pooled bits (next step) exist
         if "out" in s and "act" in r:
             assert np.array_equal(esp.packed_to_numpy(s["out"])[rows], oracle.pack_bits(r["act"])), i
     return ref[-1]["pre"]
 
 
-@pytest.mark.parametrize("batch,fused,engine", [(1, False, 0), (3, False, 0), (1, True, 0), (12, True, 0),
-                                                (1, True, 1), (12, True, 1), (12, True, 2)])
-def test_cnn_forward(batch, fused, engine):
+@pytest.mark.parametrize("batch,fused,engine,fuse_pool",
+                         [(1, False, 0, False), (3, False, 0, False), (1, True, 0, True), (12, True, 0, True),
+                          (1, True, 1, True), (12, True, 1, True), (12, True, 2, True), (12, True, 0, False),
+                          (2, True, 1, False)])
+def test_cnn_forward(batch, fused, engine, fuse_pool):
     layers = synth.cnn_params()
     x = synth.cnn_input(batch)
-    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True, fused=fused, engine=engine)
+    net = nets.BinaryCNN(layers, batch, EPS, device=DEV, keep_first_pre=True, fused=fused, engine=engine,
+                         fuse_pool=fuse_pool)
+    assert sum(bool(s.get("pool_after")) for s in net.steps) == (3 if fuse_pool else 0)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
     want = _check_cnn(net, x, layers, np.arange(batch))

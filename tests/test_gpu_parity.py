@@ -313,6 +313,56 @@ def test_bconv_bn_sign_pack(B, H, W, C, L2, kh, kw, stride, pad, engine):
     assert np.array_equal(esp.bconv(xp, fp, C, stride, pad, engine=engine).cpu().numpy(), pre)
 
 
+# convolution + threshold + sign + 2x2 OR max-pool in one kernel.  Cases: all three tile shapes
+# of the XOR-popcount kernel (32, 64 and 128 rows), the pooled widths of the Sec. 6.3 network
+# (32, 16, 8), a ragged last tile (M not a multiple of the tile), L2 with a partial last word,
+# a 2-pixel-wide output, stride 2, and the largest fusable width (64).
+POOL_CONV_CASES = [
+    (1, 32, 32, 128, 128, 3, 3, 1, 1),     # batch 1, W2 = 32: forced onto 64-row tiles
+    (1, 16, 16, 256, 256, 3, 3, 1, 1),     # W2 = 16: 32-row tiles
+    (3, 8, 8, 512, 512, 3, 3, 1, 1),       # W2 = 8
+    (40, 32, 32, 128, 256, 3, 3, 1, 1),    # 128-row tiles, several K stages
+    (5, 16, 16, 128, 100, 3, 3, 1, 1),     # partial last word, ragged tile count
+    (3, 4, 2, 128, 70, 3, 3, 1, 1),        # W2 = 2, H2 = 4
+    (2, 16, 8, 128, 64, 3, 3, 2, 1),       # stride 2: H2 = 8, W2 = 4
+    (1, 6, 64, 128, 64, 3, 3, 1, 1),       # W2 = 64: 128-row tiles although the product is small
+    (7, 2, 2, 256, 192, 1, 1, 1, 0),       # 1x1 filter, one pooled pixel per image
+]
+
+
+@pytest.mark.parametrize("engine", [0, 1, 2])
+@pytest.mark.parametrize("B,H,W,C,L2,kh,kw,stride,pad", POOL_CONV_CASES)
+def test_bconv_bn_sign_pack_pool2(B, H, W, C, L2, kh, kw, stride, pad, engine):
+    rng = np.random.default_rng(B + 10 * H + 100 * C + kh + 1000 * L2 + 11)
+    x = _pm1(rng, (B, H, W, C))
+    f = _pm1(rng, (L2, kh, kw, C))
+    bnp = synth.bn_params(rng, L2)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(kh * kw * C)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    assert esp.bconv_pool2_fusable(H, W, C, kh, kw, stride, pad)
+    xp, fp = _packed_dev(x), _packed_dev(f)
+    got = esp.bconv_bn_sign_pack_pool2(xp, fp, C, torch.from_numpy(thr).to(DEV),
+                                       esp.to_packed_tensor(flip, DEV), stride, pad, engine=engine)
+    act = oracle.bn_sign(oracle.conv_pm1(x, f, stride, pad, -1), bnp, synth.BN_EPS)
+    want = oracle.pack_bits(oracle.maxpool_pm1(act, 2, 2))
+    assert got.shape == want.shape
+    assert np.array_equal(esp.packed_to_numpy(got), want)
+
+
+def test_bconv_pool2_rejects_shapes_it_cannot_fuse():
+    assert not esp.bconv_pool2_fusable(32, 32, 64, 3, 3, 1, 1)     # lowered-matrix path
+    assert not esp.bconv_pool2_fusable(7, 8, 128, 3, 3, 1, 1)      # odd output height
+    assert not esp.bconv_pool2_fusable(8, 12, 128, 3, 3, 1, 1)     # width not a power of two
+    assert not esp.bconv_pool2_fusable(8, 128, 128, 3, 3, 1, 1)    # a row pair exceeds the tile
+    rng = np.random.default_rng(3)
+    x = _packed_dev(_pm1(rng, (1, 8, 12, 128)))
+    f = _packed_dev(_pm1(rng, (64, 3, 3, 128)))
+    thr = torch.zeros(64, dtype=torch.int32, device=DEV)
+    flip = torch.zeros(1, dtype=esp.PACKED, device=DEV)
+    with pytest.raises(esp.EspressoError):
+        esp.bconv_bn_sign_pack_pool2(x, f, 128, thr, flip, 1, 1)
+
+
 # ------------------------------------------------------------------------------ zero-padding correction
 PADCORR_CASES = [(2, 5, 6, 128, 7, 3, 3, 1, 1), (2, 7, 5, 192, 5, 3, 3, 2, 1), (1, 6, 6, 100, 9, 3, 3, 1, 1),
                  (2, 9, 7, 256, 64, 5, 3, 2, 2), (3, 32, 32, 128, 128, 3, 3, 1, 1), (2, 8, 8, 64, 12, 3, 3, 1, 0),
