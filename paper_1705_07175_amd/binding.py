@@ -29,7 +29,7 @@ EXPORTS = (
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
-    "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2",
+    "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2"
 )
 
 _lib = None
@@ -117,6 +117,19 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
     return t.data_ptr()
 
 
+def _out(out, shape, dtype: torch.dtype, device) -> torch.Tensor:
+    """The result buffer: a fresh one, or the caller's after a size check (the kernels trust it)."""
+    shape = tuple(int(d) for d in shape)
+    if out is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    n = 1
+    for d in shape:
+        n *= d
+    if out.numel() != n:
+        raise ValueError("out has %d elements, the result has %d %s" % (out.numel(), n, shape))
+    return out
+
+
 def words(k: int) -> int:
     """64-bit words per packed row of ``k`` values."""
     return (int(k) + 63) // 64
@@ -132,8 +145,7 @@ def pack_f32(src: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor
     p = _dev(src, torch.float32, "src")
     k = src.shape[-1]
     rows = src.numel() // k if k else 0
-    if out is None:
-        out = torch.empty(src.shape[:-1] + (words(k),), dtype=PACKED, device=src.device)
+    out = _out(out, src.shape[:-1] + (words(k),), PACKED, src.device)
     _check(lib().esp_pack_f32(p, _dev(out, PACKED, "out"), rows, k, _stream()), "esp_pack_f32")
     return out
 
@@ -144,8 +156,7 @@ def bgemm(a: torch.Tensor, b: torch.Tensor, k: int, out: torch.Tensor | None = N
     M, N = a.shape[0], b.shape[0]
     if a.dim() != 2 or b.dim() != 2 or a.shape[1] != words(k) or b.shape[1] != words(k):
         raise ValueError("a and b must be [rows][ceil(k/64)]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    out = _out(out, (M, N), torch.int32, a.device)
     _check(lib().esp_bgemm(pa, pb, _dev(out, torch.int32, "out"), M, N, int(k), _stream()), "esp_bgemm")
     return out
 
@@ -156,8 +167,7 @@ def bgemm_mfma(a: torch.Tensor, b: torch.Tensor, k: int, out: torch.Tensor | Non
     M, N = a.shape[0], b.shape[0]
     if a.dim() != 2 or b.dim() != 2 or a.shape[1] != words(k) or b.shape[1] != words(k):
         raise ValueError("a and b must be [rows][ceil(k/64)]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    out = _out(out, (M, N), torch.int32, a.device)
     _check(lib().esp_bgemm_mfma(pa, pb, _dev(out, torch.int32, "out"), M, N, int(k), _stream()),
            "esp_bgemm_mfma")
     return out
@@ -175,8 +185,7 @@ def unroll(x: torch.Tensor, c: int, kh: int, kw: int, stride: int, pad: int,
     if Cw != words(c):
         raise ValueError("last dim must be ceil(c/64)")
     H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
-    if out is None:
-        out = torch.empty((B * max(H2, 0) * max(W2, 0), kh * kw * Cw), dtype=PACKED, device=x.device)
+    out = _out(out, (B * max(H2, 0) * max(W2, 0), kh * kw * Cw), PACKED, x.device)
     _check(lib().esp_unroll(p, _dev(out, PACKED, "out"), B, H, W, int(c), kh, kw, stride, pad, _stream()),
            "esp_unroll")
     return out
@@ -199,8 +208,7 @@ def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
     if workspace is None:
         need = bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad)
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    if out is None:
-        out = torch.empty((B, max(H2, 0), max(W2, 0), L2), dtype=torch.int32, device=x.device)
+    out = _out(out, (B, max(H2, 0), max(W2, 0), L2), torch.int32, x.device)
     fn = lib().esp_bconv_mfma if engine == ENGINE_MFMA else lib().esp_bconv
     _check(fn(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
               _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
@@ -221,8 +229,7 @@ def bgemm_bn_sign_pack(a: torch.Tensor, b: torch.Tensor, k: int, thr: torch.Tens
         raise ValueError("a and b must be [rows][ceil(k/64)]")
     if thr.numel() != N or flip.numel() != words(N):
         raise ValueError("thr/flip size mismatch")
-    if out is None:
-        out = torch.empty((M, words(N)), dtype=PACKED, device=a.device)
+    out = _out(out, (M, words(N)), PACKED, a.device)
     _check(lib().esp_bgemm_bn_sign_pack(pa, pb, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
                                         _dev(out, PACKED, "out"), M, N, int(k), int(engine), _stream()),
            "esp_bgemm_bn_sign_pack")
@@ -242,8 +249,7 @@ def bconv_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, c: int, thr: torch.T
     if workspace is None and bconv_needs_workspace(c):
         need = bconv_workspace_bytes(B, H, W, c, kh, kw, stride, pad)
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    if out is None:
-        out = torch.empty((B, max(H2, 0), max(W2, 0), words(L2)), dtype=PACKED, device=x.device)
+    out = _out(out, (B, max(H2, 0), max(W2, 0), words(L2)), PACKED, x.device)
     ws_ptr = _dev(workspace, torch.uint8, "workspace") if workspace is not None else None
     ws_len = workspace.numel() if workspace is not None else 0
     _check(lib().esp_bconv_bn_sign_pack(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
@@ -267,10 +273,7 @@ def bconv_bn_sign_pack_pool2(x: torch.Tensor, filt: torch.Tensor, c: int, thr: t
     if Cw != words(c) or Cw2 != Cw or thr.numel() != L2 or flip.numel() != words(L2):
         raise ValueError("shape mismatch")
     H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
-    if out is None:
-        out = torch.empty((B, max(H2, 0) // 2, max(W2, 0) // 2, words(L2)), dtype=PACKED, device=x.device)
-    elif out.numel() != B * (H2 // 2) * (W2 // 2) * words(L2):
-        raise ValueError("out has the wrong size")
+    out = _out(out, (B, max(H2, 0) // 2, max(W2, 0) // 2, words(L2)), PACKED, x.device)
     _check(lib().esp_bconv_bn_sign_pack_pool2(px, pf, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
                                               _dev(out, PACKED, "out"), B, H, W, int(c), L2, kh, kw, stride,
                                               pad, int(engine), _stream()), "esp_bconv_bn_sign_pack_pool2")
@@ -285,8 +288,7 @@ def pad_correction(filt: torch.Tensor, c: int, h: int, w: int, stride: int, pad:
     if Cw != words(c):
         raise ValueError("channel words mismatch")
     H2, W2 = conv_out(h, kh, stride, pad), conv_out(w, kw, stride, pad)
-    if out is None:
-        out = torch.empty((max(H2, 0), max(W2, 0), L2), dtype=torch.int32, device=filt.device)
+    out = _out(out, (max(H2, 0), max(W2, 0), L2), torch.int32, filt.device)
     _check(lib().esp_pad_correction(pf, _dev(out, torch.int32, "out"), h, w, int(c), L2, kh, kw, stride, pad,
                                     _stream()), "esp_pad_correction")
     return out
@@ -296,7 +298,7 @@ def add_pad_correction(x: torch.Tensor, corr: torch.Tensor, h: int, w: int, kh: 
                        stride: int, pad: int) -> torch.Tensor:
     """``esp_add_pad_correction``: x int32 [B][H2][W2][L2] += corr [H2][W2][L2], in place."""
     B, H2, W2, L2 = x.shape
-    if tuple(corr.shape) != (H2, W2, L2):
+    if tuple(corr.shape) != (H2, W2, L2) or (H2, W2) != (conv_out(h, kh, stride, pad), conv_out(w, kw, stride, pad)):
         raise ValueError("correction shape mismatch")
     _check(lib().esp_add_pad_correction(_dev(x, torch.int32, "x"), _dev(corr, torch.int32, "corr"), B, h, w,
                                         L2, kh, kw, stride, pad, _stream()), "esp_add_pad_correction")
@@ -322,8 +324,7 @@ def bn_sign_pack(x: torch.Tensor, thr: torch.Tensor, flip: torch.Tensor,
     rows = x.numel() // C if C else 0
     if thr.numel() != C or flip.numel() != words(C):
         raise ValueError("thr/flip size mismatch")
-    if out is None:
-        out = torch.empty(x.shape[:-1] + (words(C),), dtype=PACKED, device=x.device)
+    out = _out(out, x.shape[:-1] + (words(C),), PACKED, x.device)
     _check(lib().esp_bn_sign_pack(px, _dev(thr, torch.int32, "thr"), _dev(flip, PACKED, "flip"),
                                   _dev(out, PACKED, "out"), rows, C, _stream()), "esp_bn_sign_pack")
     return out
@@ -337,8 +338,7 @@ def bmaxpool(x: torch.Tensor, c: int, win: int = 2, stride: int = 2,
     if Cw != words(c):
         raise ValueError("last dim must be ceil(c/64)")
     H2, W2 = (H - win) // stride + 1, (W - win) // stride + 1
-    if out is None:
-        out = torch.empty((B, max(H2, 0), max(W2, 0), Cw), dtype=PACKED, device=x.device)
+    out = _out(out, (B, max(H2, 0), max(W2, 0), Cw), PACKED, x.device)
     _check(lib().esp_bmaxpool(p, _dev(out, PACKED, "out"), B, H, W, int(c), win, stride, _stream()),
            "esp_bmaxpool")
     return out
@@ -351,8 +351,7 @@ def dense_f32(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None)
     N, K2 = w.shape
     if K != K2:
         raise ValueError("K mismatch")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    out = _out(out, (M, N), torch.float32, x.device)
     _check(lib().esp_dense_f32(px, pw, _dev(out, torch.float32, "out"), M, N, K, _stream()), "esp_dense_f32")
     return out
 
@@ -366,8 +365,7 @@ def conv_f32(x: torch.Tensor, filt: torch.Tensor, stride: int, pad: int,
     if C != C2:
         raise ValueError("C mismatch")
     H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
-    if out is None:
-        out = torch.empty((B, max(H2, 0), max(W2, 0), L2), dtype=torch.float32, device=x.device)
+    out = _out(out, (B, max(H2, 0), max(W2, 0), L2), torch.float32, x.device)
     _check(lib().esp_conv_f32(px, pf, _dev(out, torch.float32, "out"), B, H, W, C, L2, kh, kw, stride, pad,
                               _stream()), "esp_conv_f32")
     return out
@@ -392,8 +390,7 @@ def bn_sign_pack_f32(x: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
     rows = x.numel() // C if C else 0
     if thr.numel() != C or sgn.numel() != C:
         raise ValueError("thr/sgn size mismatch")
-    if out is None:
-        out = torch.empty(x.shape[:-1] + (words(C),), dtype=PACKED, device=x.device)
+    out = _out(out, x.shape[:-1] + (words(C),), PACKED, x.device)
     _check(lib().esp_bn_sign_pack_f32(px, _dev(thr, torch.float32, "thr"), _dev(sgn, torch.float32, "sgn"),
                                       _dev(out, PACKED, "out"), rows, C, _stream()), "esp_bn_sign_pack_f32")
     return out
@@ -410,8 +407,9 @@ def conv_f32_bn_sign_pack(x: torch.Tensor, filt: torch.Tensor, thr: torch.Tensor
     if C != C2 or thr.numel() != L2 or sgn.numel() != L2:
         raise ValueError("shape mismatch")
     H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
-    if out is None:
-        out = torch.empty((B, max(H2, 0), max(W2, 0), words(L2)), dtype=PACKED, device=x.device)
+    out = _out(out, (B, max(H2, 0), max(W2, 0), words(L2)), PACKED, x.device)
+    if pre is not None:
+        _out(pre, (B, max(H2, 0), max(W2, 0), L2), torch.float32, x.device)
     ppre = _dev(pre, torch.float32, "pre") if pre is not None else None
     _check(lib().esp_conv_f32_bn_sign_pack(px, pf, _dev(thr, torch.float32, "thr"),
                                            _dev(sgn, torch.float32, "sgn"), _dev(out, PACKED, "out"), ppre,
@@ -427,8 +425,7 @@ def bitplane_pack_u8(x: torch.Tensor, out: torch.Tensor | None = None) -> torch.
     k = x.shape[-1]
     outer = x.shape[0]
     inner = x.numel() // (outer * k) if outer and k else 1
-    if out is None:
-        out = torch.empty((outer, 8) + tuple(x.shape[1:-1]) + (words(k),), dtype=PACKED, device=x.device)
+    out = _out(out, (outer, 8) + tuple(x.shape[1:-1]) + (words(k),), PACKED, x.device)
     _check(lib().esp_bitplane_pack_u8(p, _dev(out, PACKED, "out"), outer, inner, k, _stream()),
            "esp_bitplane_pack_u8")
     return out
@@ -438,8 +435,7 @@ def row_sums(w: torch.Tensor, k: int, out: torch.Tensor | None = None) -> torch.
     """``esp_row_sums``: packed weights [N][...] holding ``k`` true values per row -> int32 [N]."""
     pw = _dev(w, PACKED, "w")
     N = w.shape[0]
-    if out is None:
-        out = torch.empty((N,), dtype=torch.int32, device=w.device)
+    out = _out(out, (N,), torch.int32, w.device)
     _check(lib().esp_row_sums(pw, _dev(out, torch.int32, "out"), N, w.numel() // N, int(k), _stream()),
            "esp_row_sums")
     return out
@@ -452,8 +448,7 @@ def bitplane_combine(d: torch.Tensor, wsum: torch.Tensor, out: torch.Tensor | No
     if d.shape[1] != 8 or wsum.numel() != N:
         raise ValueError("d must be [outer][8][...][N]")
     inner = d.numel() // (outer * 8 * N) if outer else 1
-    if out is None:
-        out = torch.empty((outer,) + tuple(d.shape[2:]), dtype=torch.int32, device=d.device)
+    out = _out(out, (outer,) + tuple(d.shape[2:]), torch.int32, d.device)
     _check(lib().esp_bitplane_combine(pd, _dev(wsum, torch.int32, "wsum"), _dev(out, torch.int32, "out"),
                                       outer, inner, N, _stream()), "esp_bitplane_combine")
     return out

@@ -478,6 +478,7 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
 }
 
 constexpr size_t kGemvLdsBytes = 64 * 1024;
+constexpr int kGemvMaxM = 8;   // rows of A the small-M kernels take
 
 template <int MS, bool VEC16>
 static int launch_gemv2(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
@@ -514,6 +515,137 @@ static int launch_gemv(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t
                  : launch_gemv2<MS, false>(A, B, C, M, N, K_true, row_words, stream);
 }
 
+// ---------------------------------------------------------------------------------
+// Small-M product with the folded batch-norm threshold + sign in the epilogue (one image at
+// a time, Sec. 6.2 "Optimized kernels"): a block owns 64 consecutive rows of B, i.e. exactly
+// one packed output word per row of A, so no int32 score and no second launch is needed.
+// The block's waves split the 64 rows; inside a wave lpr lanes share a row as in
+// bgemv_kernel, and every lane keeps PASSES rows in flight (PASSES = lpr * waves / 64).
+// ---------------------------------------------------------------------------------
+template <int MS, bool VEC16, int PASSES>
+__global__ __launch_bounds__(1024)
+void bgemv_bits_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B,
+                       const int32_t *__restrict__ thr, const uint64_t *__restrict__ flip,
+                       uint64_t *__restrict__ out, int M, int N, int K_true, int row_words, int lpr)
+{
+    using CK = Chunk<VEC16>;
+    using chunk_t = typename CK::type;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    chunk_t *As = reinterpret_cast<chunk_t *>(smem_raw);
+    __shared__ unsigned char decided[MS][64];   // (m, row of the block) -> dot >= thr
+
+    const int nch = row_words / CK::words;
+    const chunk_t *Ag = reinterpret_cast<const chunk_t *>(A);
+    const chunk_t *Bg = reinterpret_cast<const chunk_t *>(B);
+
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int rpw = kWave / lpr;          // rows of B per wave pass
+    const int sub = lane / lpr;
+    const int cl = lane % lpr;
+    const int n_blk = blockIdx.x * 64;
+    // row handled in pass p: the wave owns PASSES * rpw consecutive rows
+    const int row0 = n_blk + wave * (PASSES * rpw) + sub;
+
+    // the weights are the long pole: start on them before A is staged
+    chunk_t b[PASSES];
+    int t[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int row = row0 + p * rpw;
+        b[p] = (row < N && cl < nch) ? Bg[(int64_t)row * nch + cl] : CK::zero();
+        t[p] = row < N ? thr[row] : 0;
+    }
+    for (int i = threadIdx.x; i < MS * nch; i += blockDim.x)
+        As[i] = (i / nch < M) ? Ag[i] : CK::zero();
+    __syncthreads();
+
+    int acc[PASSES][MS];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+            acc[p][m] = 0;
+    for (int c = cl; c < nch; c += lpr) {
+        chunk_t nxt[PASSES];
+        const int cn = c + lpr;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = row0 + p * rpw;
+            nxt[p] = (row < N && cn < nch) ? Bg[(int64_t)row * nch + cn] : CK::zero();
+        }
+#pragma unroll
+        for (int m = 0; m < MS; ++m) {
+            const chunk_t a = As[m * nch + c];
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p)
+                acc[p][m] += CK::mism(a, b[p]);
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+            b[p] = nxt[p];
+    }
+    for (int off = lpr >> 1; off > 0; off >>= 1) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+#pragma unroll
+            for (int m = 0; m < MS; ++m)
+                acc[p][m] += __shfl_xor(acc[p][m], off, kWave);
+    }
+    if (cl == 0) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = row0 + p * rpw;
+#pragma unroll
+            for (int m = 0; m < MS; ++m)
+                decided[m][row - n_blk] = row < N && K_true - 2 * acc[p][m] >= t[p];
+        }
+    }
+    __syncthreads();
+    for (int m = wave; m < M; m += blockDim.x / kWave) {
+        const uint64_t word = __ballot(decided[m][lane] != 0);
+        if (lane == 0)
+            out[(int64_t)m * gridDim.x + blockIdx.x] = word ^ flip[blockIdx.x];
+    }
+}
+
+template <int MS, bool VEC16>
+static int launch_gemv_bits2(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
+                             uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                             hipStream_t stream)
+{
+    const int nch = (int)(row_words / (VEC16 ? 2 : 1));
+    int lpr = 1;
+    while (lpr < kWave && lpr < nch)
+        lpr <<= 1;
+    // 64 rows per block = waves * PASSES * (64 / lpr): up to 16 waves, then rows in flight per lane
+    const int waves = lpr < 16 ? lpr : 16;
+    const int passes = lpr / waves;   // 1, 2 or 4
+    const dim3 grid((unsigned)ceil_div(N, 64)), block((unsigned)(waves * kWave));
+    const size_t lds = (size_t)MS * row_words * 8;
+#define ESP_GEMV_BITS(P)                                                                                 \
+    hipLaunchKernelGGL((bgemv_bits_kernel<MS, VEC16, P>), grid, block, lds, stream, A, B, thr, flip, out, \
+                       (int)M, (int)N, (int)K_true, (int)row_words, lpr)
+    if (passes == 1)
+        ESP_GEMV_BITS(1);
+    else if (passes == 2)
+        ESP_GEMV_BITS(2);
+    else
+        ESP_GEMV_BITS(4);
+#undef ESP_GEMV_BITS
+    return launch_status();
+}
+
+template <int MS>
+static int launch_gemv_bits(const uint64_t *A, const uint64_t *B, const int32_t *thr, const uint64_t *flip,
+                            uint64_t *out, int64_t M, int64_t N, int64_t K_true, int64_t row_words,
+                            hipStream_t stream)
+{
+    const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
+    return vec16 ? launch_gemv_bits2<MS, true>(A, B, thr, flip, out, M, N, K_true, row_words, stream)
+                 : launch_gemv_bits2<MS, false>(A, B, thr, flip, out, M, N, K_true, row_words, stream);
+}
+
 int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
                  int64_t K_true, int64_t row_words, hipStream_t stream)
 {
@@ -540,10 +672,22 @@ int bgemm_bits_launch(const uint64_t *A, const uint64_t *B, const int32_t *thr, 
 {
     if (M == 0)
         return ESP_OK;
-    if (resolve_engine(engine, M, N, K_true) == ESP_ENGINE_MFMA)
-        return bgemm_mfma_launch(A, B, nullptr, thr, flip, out, M, N, K_true, row_words, stream);
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29))
         return ESP_ESHAPE;
+    // few rows: stream B once (as long as the packed rows of A fit in LDS), unless the caller
+    // insists on the matrix cores
+    const int ms = M <= 1 ? 1 : (M <= 2 ? 2 : (M <= 4 ? 4 : 8));
+    if (engine != ESP_ENGINE_MFMA && M <= kGemvMaxM && (size_t)ms * row_words * 8 <= kGemvLdsBytes) {
+        if (ms == 1)
+            return launch_gemv_bits<1>(A, B, thr, flip, out, M, N, K_true, row_words, stream);
+        if (ms == 2)
+            return launch_gemv_bits<2>(A, B, thr, flip, out, M, N, K_true, row_words, stream);
+        if (ms == 4)
+            return launch_gemv_bits<4>(A, B, thr, flip, out, M, N, K_true, row_words, stream);
+        return launch_gemv_bits<8>(A, B, thr, flip, out, M, N, K_true, row_words, stream);
+    }
+    if (resolve_engine(engine, M, N, K_true) == ESP_ENGINE_MFMA)
+        return bgemm_mfma_launch(A, B, nullptr, thr, flip, out, M, N, K_true, row_words, stream);
     TileOut o;
     o.bits = out;
     o.thr = thr;

@@ -88,7 +88,7 @@ class BinaryMLP:
         for i in range(1, len(self.wp)):
             if self.bn[i] is None:
                 esp.bgemm(self.act[i - 1], self.wp[i], self.sizes[i], out=self.pre[i])
-            elif self.fused and self.batch > 8:
+            elif self.fused:
                 # threshold + sign + pack in the product's epilogue: no int32 round trip
                 esp.bgemm_bn_sign_pack(self.act[i - 1], self.wp[i], self.sizes[i], self.bn[i].thr,
                                        self.bn[i].flip, out=self.act[i], engine=self.engine)
@@ -199,7 +199,7 @@ class BinaryCNN:
                 a = cur.reshape(self.batch, -1)   # flatten in storage order: free
                 if s["bn"] is None:
                     cur = esp.bgemm(a, s["w"], s["k"], out=s["pre"])
-                elif self.fused and self.batch > 8:
+                elif self.fused:
                     cur = esp.bgemm_bn_sign_pack(a, s["w"], s["k"], s["bn"].thr, s["bn"].flip, out=s["out"],
                                                  engine=self.engine)
                 else:

@@ -63,6 +63,22 @@ def test_mlp_forward(batch):
     assert np.array_equal(scores, ref[3]["pre"])
 
 
+@pytest.mark.parametrize("batch", [1, 5, 8])
+def test_mlp_forward_fused_small_batch(batch):
+    # at most 8 rows: the binary layers run as the small-M product with the threshold epilogue
+    layers = synth.mlp_params()
+    x = synth.mlp_input(batch)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=True)
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    ref = onets.mlp_forward(x, layers, EPS)
+    act0 = _check_first_layer(net.pre[0].cpu().numpy(), esp.packed_to_numpy(net.act[0]), ref[0],
+                              layers[0]["bn"], 4096)
+    ref = onets.mlp_forward(x, layers, EPS, first_act=act0)
+    for i in (1, 2):
+        assert np.array_equal(esp.packed_to_numpy(net.act[i]), oracle.pack_bits(ref[i]["act"])), i
+    assert np.array_equal(scores, ref[3]["pre"])
+
+
 @pytest.mark.parametrize("batch", [1, 70])
 def test_mlp_forward_bitplane_first_layer(batch):
     # 8-bit input, first layer by bit-planes (Eq. 3): integer everywhere, so the whole network

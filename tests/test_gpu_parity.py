@@ -254,8 +254,14 @@ def test_bn_sign_pack(rows, C, K):
 
 
 # ------------------------------------------------------------------------------ fused epilogues
+# M <= 8 takes the small-M kernel (64 rows of B per block): every row-split it has (K from one
+# chunk per row to several chunks per lane), odd word counts, ragged N, and M = 1, 2, 4, 8 and between
+SMALL_M_BITS = [(1, 4096, 4096), (2, 100, 70), (3, 1024, 1024), (4, 130, 192), (5, 7, 1000), (8, 1024, 8192),
+                (8, 65, 1), (7, 33, 200), (1, 1000, 65472), (2, 129, 20000), (6, 64, 640), (1, 10, 320)]
+
+
 @pytest.mark.parametrize("engine", [0, 1])
-@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (9, 10, 4096), (64, 4096, 1024), (130, 70, 200), (257, 513, 1152),
+@pytest.mark.parametrize("M,N,K", SMALL_M_BITS + [(1, 64, 64), (9, 10, 4096), (64, 4096, 1024), (130, 70, 200), (257, 513, 1152),
                                    (1000, 128, 1152), (5, 1024, 8192), (1024, 1024, 1024)])
 def test_bgemm_bn_sign_pack(M, N, K, engine):
     rng = np.random.default_rng(M * 31 + N * 17 + K)
