@@ -32,6 +32,7 @@ CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
 # One v_xor_b32 + one accumulating v_bcnt_u32_b32 per lane handle 32 binary MACs = 64 bop.
 VALU_PEAK_TBOPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ * 64 / 2 / 1e12      # 1258.3 Tbop/s
 HBM_PEAK_GBS = 8000.0
+MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 MFMA
 MFMA_FP4_PEAK_TOPS = 10100.0   # dense fp4/fp6 MFMA, TFLOP/s; one binary MAC = 2 flop = 2 bop
 
 
@@ -185,7 +186,7 @@ def main() -> int:
     return 0
 
 
-SUPPORTING = ("copy", "pack", "bn_sign_pack", "unroll", "bmaxpool", "bgemv", "bgemv_1g", "bconv_cfg2",
+SUPPORTING = ("copy", "pack", "bn_sign_pack", "unroll", "bmaxpool", "bgemv", "bgemv_1g", "bconv_cfg2", "conv1_b256",
               "bconv_conv2_b256", "bconv_conv4_b256", "bconv_conv6_b256",
               "bconv_conv2_b256_mfma", "bconv_conv4_b256_mfma", "bconv_conv6_b256_mfma")
 
@@ -281,6 +282,22 @@ def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3)
         out.append({"kernel": "bconv (unroll + bgemm)", "workload": "config 2: [32][32][32][128] * 128 x 3x3x128",
                     "ms": round(ms, 5), "bound": "alu", "achieved": round(tb, 2),
                     "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s", "frac": round(tb / VALU_PEAK_TBOPS, 4)})
+    if want("conv1_b256"):
+        # the CNN's real-valued first layer at batch 256 (3x3x3 -> 128, fp32 matrix cores), fused
+        # float threshold + sign + pack: floats in, bits out
+        b, h, l2 = 256, 32, 128
+        xin = torch.rand((b, h, h, 3), device=dev, generator=g)
+        filt = (torch.randint(0, 2, (l2, 3, 3, 3), device=dev, generator=g) * 2 - 1).to(torch.float32)
+        bnp = synth.bn_params(synth.rng_for(2, 9), l2)
+        thr_np, sgn_np = esp.bn_fold_f32(*bnp, synth.BN_EPS)
+        thr, sgn = torch.from_numpy(thr_np).to(dev), torch.from_numpy(sgn_np).to(dev)
+        bits = torch.empty((b, h, h, l2 // 64), dtype=esp.PACKED, device=dev)
+        ms, _ = _events_ms(lambda: esp.conv_f32_bn_sign_pack(xin, filt, thr, sgn, 1, 1, out=bits),
+                           steps, warmup, torch)
+        tf = 2.0 * b * h * h * l2 * 27 / (ms * 1e-3) / 1e12
+        out.append({"kernel": "conv_f32_bn_sign_pack (3x3x3, fp32 MFMA)", "workload": "CNN conv1 at batch 256",
+                    "ms": round(ms, 5), "bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_FP32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(tf / MFMA_FP32_PEAK_TFLOPS, 4)})
     # the CNN's second and sixth layers at batch 256, fused threshold epilogue (bits out)
     for name, h, c, l2 in (("bconv_conv2_b256", 32, 128, 128), ("bconv_conv4_b256", 16, 256, 256),
                            ("bconv_conv6_b256", 8, 512, 512)):

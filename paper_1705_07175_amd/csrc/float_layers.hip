@@ -1,8 +1,9 @@
 // Real-valued first layer in fp32 (the non-binary variant of a layer, Sec. 3 of
 // arXiv 1705.07175): the networks of Sec. 6.2 / 6.3 start from real-valued images, so
 // their first dense / convolutional layer multiplies floats by +-1 weights.  These are
-// supporting kernels, kept simple: an LDS-tiled SGEMM, a wave-per-output GEMV for tiny
-// batches and a direct convolution with the filters transposed in LDS.
+// supporting kernels: an LDS-tiled SGEMM, a wave-per-output GEMV for tiny batches, a
+// direct convolution with the filters transposed in LDS for general shapes, and the 3x3x3
+// first layer of the CIFAR-10 network on the fp32 matrix cores.
 #include "esp_internal.h"
 
 namespace esp {
@@ -141,101 +142,200 @@ void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ fil
     }
 }
 
-// Fast path for small, compile-time filter shapes at stride 1 (the 3x3x3 first layer of the
-// Sec. 6.3 network): lane = output channel with its KH*KW*C filter weights in registers; a
-// wave owns a strip of PIX consecutive output pixels of one output row.  The wave first
-// copies the strip's input window (KH rows x (PIX+KW-1) pixels x C, zeros outside the image)
-// into its private LDS slice, then every lane reads the whole window back with broadcast
-// 16-byte LDS reads, so the inner loop is KH*KW*C register-to-register fused multiply-adds
-// per output with no address arithmetic.  The 64 lanes store 256 contiguous bytes per pixel.
-// A wave walks all strips of its output row, so the weights are fetched once per row.
-// With FUSE the folded batch-norm threshold + sign is applied in the epilogue: the 64-lane
-// comparison mask of a pixel is its packed word, so only bits leave the kernel (the
-// pre-activations are written as well only if `out` is given).
-template <int C, int KH, int KW, int PIX, bool FUSE>
-__global__ __launch_bounds__(256)
-void conv_f32_lane_channel_kernel(const float *__restrict__ in, const float *__restrict__ filt,
-                                  float *__restrict__ out, const float *__restrict__ thr,
-                                  const float *__restrict__ sgn, uint64_t *__restrict__ bits,
-                                  int H, int W, int L2, int pad, int H2, int W2, int cgroups, int tasks)
+// Fast path for the 3x3x3 first layer of the Sec. 6.3 network at stride 1, on the fp32 matrix
+// cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation, twice the rate of the
+// unpacked vector FMA).  The layer is the dense contraction
+//   out[pixel][l2] = sum_k window[pixel][k] * filt[l2][k],  k = (dy, dx, c) < 27 (padded to 28),
+// so a wave owns a strip of 32 consecutive output pixels of one output row (= the 32 rows of
+// the MFMA's A operand) and NB blocks of 32 output channels (the columns):
+//  * the wave copies the strip's input window (3 rows x 34 pixels x 3 channels, zeros outside
+//    the image) into its private LDS slice; lane (pixel p, k-half h) reads element
+//    (p, k = 2 s + h) of the lowered window for step s straight from there;
+//  * the weights of the wave's channels stay in registers as B operands for all its strips;
+//  * with FUSE the per-channel sign of the folded batch-norm is multiplied into the weights
+//    (exact), so the epilogue is one compare per accumulator whose 64-lane mask holds the
+//    bits of two pixels x 32 channels; only packed words leave the kernel (the pre-
+//    activations are written as well only if `pre` is given).
+// MFMA result layout: lane -> column lane % 32, register r -> row 8 (r / 4) + 4 (lane / 32) + r % 4.
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// v or +0.0f.  A bit mask instead of a select keeps the load that produced v unconditional
+// (from a clamped, always valid address), so that independent loads are issued back to back
+// rather than each inside its own branch with its own wait.
+__device__ __forceinline__ float keep_if(float v, bool keep)
 {
-    constexpr int T = KH * KW * C;
-    constexpr int RL = (PIX + KW - 1) * C;          // floats per window row
-    constexpr int RLP = (RL + 3) / 4 * 4;           // padded to whole float4s
-    constexpr int WIN = KH * RLP;
-    __shared__ __align__(16) float win_all[4][WIN];
+    return __uint_as_float(__float_as_uint(v) & (keep ? 0xffffffffu : 0u));
+}
+
+template <int NB, bool FUSE>
+__global__ __launch_bounds__(256, 2)
+void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict__ filt,
+                           float *__restrict__ pre, const float *__restrict__ thr,
+                           const float *__restrict__ sgn, uint64_t *__restrict__ bits,
+                           int H, int W, int L2, int pad, int H2, int W2, int strips, int rows_strips,
+                           int tasks)
+{
+    constexpr int T = 27, KS = 14;                 // taps * channels, k-steps of 2
+    constexpr int PIX = 32, WROW = (PIX + 2) * 3;  // floats per window row
+    constexpr int WIN = 3 * WROW;
+    constexpr int kSlots = NB < 2 ? 2 : NB;        // 32-bit slots per pixel in the word table
+    __shared__ float win_all[4][WIN + 2];          // + a zero slot for the padding k = 27, + scratch
+    __shared__ __align__(16) uint32_t word_all[4][PIX * kSlots];
 
     const int lane = threadIdx.x % kWave;
-    const int wave = threadIdx.x / kWave;
-    const int task = blockIdx.x * (blockDim.x / kWave) + wave;   // wave-uniform
-    if (task >= tasks)
-        return;
-    // task -> (image row bm = b*H2 + m, channel group); channel group fastest
-    const int cg = task % cgroups;
-    const int bm = task / cgroups;
-    const int m = bm % H2;
-    const int b = bm / H2;
-    const int l2 = cg * kWave + lane;
-    const bool lane_ok = l2 < L2;
-
-    float wgt[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t)
-        wgt[t] = lane_ok ? filt[l2 * T + t] : 0.0f;
-
-    float th = 0.0f, sg = 1.0f;
-    if (FUSE && lane_ok) {
-        th = thr[l2];
-        sg = sgn[l2];
-    }
-
+    // the wave index and everything derived from it (the task decomposition) stay in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int lr = lane % 32, half = lane / 32;
     float *win = win_all[wave];
-    const float *img = in + (int64_t)b * H * W * C;
-    float *orow = out + ((int64_t)bm * W2) * L2 + l2;
-    for (int n0 = 0; n0 < W2; n0 += PIX) {
-    uint64_t mine = 0;
-    // window -> LDS (zero padding applied here)
-    for (int i = lane; i < WIN; i += kWave) {
-        const int r = i / RLP, j = i % RLP;
-        const int y = m - pad + r;
-        const int x = n0 - pad + j / C;
-        float v = 0.0f;
-        if (j < RL && y >= 0 && y < H && x >= 0 && x < W)
-            v = img[(y * W + x) * C + j % C];
-        win[i] = v;
-    }
-    // LDS operations of one wave complete in order: no barrier needed for a private slice
-    float wv[WIN];
+    if (lane == 0)
+        win[WIN] = 0.0f;
+
+    // window element i = lane + 64 q of a strip: row wr, pixel wx, offset wo from the window's
+    // first element in the image (i beyond the window: a row that is never inside the image)
+    constexpr int kTrips = (WIN + kWave - 1) / kWave;
+    int wr[kTrips], wx[kTrips], wo[kTrips], wdst[kTrips];
 #pragma unroll
-    for (int q = 0; q < WIN / 4; ++q) {
-        const float4 t4 = *reinterpret_cast<const float4 *>(win + 4 * q);
-        wv[4 * q + 0] = t4.x;
-        wv[4 * q + 1] = t4.y;
-        wv[4 * q + 2] = t4.z;
-        wv[4 * q + 3] = t4.w;
+    for (int q = 0; q < kTrips; ++q) {
+        const int i = lane + q * kWave;
+        const int r = i / WROW, j = i - r * WROW;
+        wr[q] = i < WIN ? r : -(1 << 30);
+        wx[q] = j / 3;
+        wo[q] = r * W * 3 + j;
+        wdst[q] = i < WIN ? i : WIN + 1;           // WIN + 1: scratch slot
     }
 
+    // lowered-window element (pixel lr, k) sits at 93 * dy + 3 * lr + k, dy = k / 9
+    int off[KS];
 #pragma unroll
-    for (int p = 0; p < PIX; ++p) {
-        float acc = 0.0f;
+    for (int s = 0; s < KS; ++s) {
+        const int k = 2 * s + half;
+        off[s] = k < T ? 93 * (k / 9) + 3 * lr + k : WIN;
+    }
+
+    const int Cw = (L2 + 63) / 64;
+    float bw[NB][KS];
+    float th[NB], sg[NB];
+    int cur_cg = -1;
+    const int nwaves = gridDim.x * (blockDim.x / kWave);
+    const int task0 = blockIdx.x * (blockDim.x / kWave) + wave;
+
+    // The window of a strip is fetched one task ahead: its loads are in flight while the
+    // matrix cores work on the current strip.  Zero padding is applied here; window rows are
+    // contiguous runs of the image; 32-bit offsets from the image's first element
+    // (H * W * 3 < 2^31, checked by the host).
+    float wv_[kTrips];
+    auto fetch_window = [&](int task) {
+        const int rs = task % rows_strips;
+        const int bm = rs / strips;
+        const int n0 = (rs - bm * strips) * PIX;
+        const float *img = in + (int64_t)(bm / H2) * H * W * 3;
+        const int y0 = bm % H2 - pad, x0 = n0 - pad;
+        const int first = (y0 * W + x0) * 3;
 #pragma unroll
-        for (int dy = 0; dy < KH; ++dy)
+        for (int q = 0; q < kTrips; ++q) {
+            const bool inb = (unsigned)(y0 + wr[q]) < (unsigned)H && (unsigned)(x0 + wx[q]) < (unsigned)W;
+            wv_[q] = keep_if(img[inb ? first + wo[q] : 0], inb);
+        }
+    };
+    if (task0 < tasks)
+        fetch_window(task0);
+
+    for (int task = task0; task < tasks; task += nwaves) {
+        // task -> (channel group, image row bm = b * H2 + m, strip); channel group slowest
+        const int cg = task / rows_strips;
+        const int rs = task - cg * rows_strips;
+        const int bm = rs / strips;
+        const int n0 = (rs - bm * strips) * PIX;
+        if (cg != cur_cg) {     // wave-uniform
+            cur_cg = cg;
 #pragma unroll
-            for (int dx = 0; dx < KW; ++dx)
+            for (int nb = 0; nb < NB; ++nb) {
+                const int l2 = (cg * NB + nb) * 32 + lr;
+                const bool ok = l2 < L2;
+                const int l2c = ok ? l2 : 0;          // loads stay unconditional (and in flight together)
+                sg[nb] = FUSE ? sgn[l2c] : 1.0f;
+                th[nb] = FUSE ? thr[l2c] : 0.0f;
+                if (!ok) {
+                    sg[nb] = 1.0f;
+                    th[nb] = __builtin_inff();         // beyond L2: bit 0
+                }
 #pragma unroll
-                for (int c = 0; c < C; ++c)
-                    acc = fmaf(wv[dy * RLP + (p + dx) * C + c], wgt[(dy * KW + dx) * C + c], acc);
-        if ((!FUSE || out) && lane_ok && n0 + p < W2)
-            orow[(int64_t)(n0 + p) * L2] = acc;
+                for (int s = 0; s < KS; ++s) {
+                    const int k = 2 * s + half;
+                    const float wv = filt[(int64_t)l2c * T + (k < T ? k : 0)];
+                    bw[nb][s] = keep_if(sg[nb] * wv, ok && k < T);
+                }
+            }
+        }
+
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < kTrips; ++q)
+            win[wdst[q]] = wv_[q];
+        __builtin_amdgcn_wave_barrier();   // LDS operations of one wave complete in order
+        if (task + nwaves < tasks)
+            fetch_window(task + nwaves);
+
+        v16f acc[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[nb][r] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const float a = win[off[s]];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bw[nb][s], acc[nb], 0, 0, 0);
+        }
+
+        const int64_t pix0 = (int64_t)bm * W2 + n0;    // first output pixel of the strip
+        if (!FUSE || pre) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int l2 = (cg * NB + nb) * 32 + lr;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int p = 8 * (r / 4) + 4 * half + r % 4;
+                    if (l2 < L2 && n0 + p < W2)
+                        pre[(pix0 + p) * L2 + l2] = sg[nb] * acc[nb][r];   // sg = +-1: undoes the fold
+                }
+            }
+        }
         if (FUSE) {
-            const uint64_t word = __ballot(lane_ok && sg * acc >= th);
-            if (lane == p)
-                mine = word;
+            // comparison mask of register r, block nb: low half = the 32 channel bits of pixel
+            // 8 (r/4) + r%4, high half = those of that pixel + 4.  Lanes 0 and 32 drop the halves
+            // into the wave's LDS word table [pixel][block]; lane p then stores pixel p's words.
+            uint32_t *wl = word_all[wave];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                uint32_t v[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const uint64_t mask = __ballot(acc[nb][r] >= th[nb]);
+                    v[nb] = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+                }
+                const int p = 8 * (r / 4) + 4 * half + r % 4;
+                if (lr == 0) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        wl[p * kSlots + nb] = v[nb];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < PIX && n0 + lane < W2) {
+#pragma unroll
+                for (int q = 0; q < (NB + 1) / 2; ++q) {
+                    const int w = cg * ((NB * 32) / 64) + q;
+                    const uint64_t lo = wl[lane * kSlots + 2 * q];
+                    const uint64_t hi = 2 * q + 1 < NB ? wl[lane * kSlots + 2 * q + 1] : 0u;
+                    if (w < Cw)
+                        bits[(pix0 + lane) * Cw + w] = lo | (hi << 32);
+                }
+            }
         }
     }
-    if (FUSE && lane < PIX && n0 + lane < W2)
-        bits[((int64_t)bm * W2 + n0 + lane) * cgroups + cg] = mine;
-    } // strips
 }
 
 } // namespace esp
@@ -284,20 +384,38 @@ static int conv_f32_launch(const float *in, const float *filt, float *out, const
     if (!(C == 3 && kh == 3 && kw == 3 && stride == 1 && (int64_t)H * W * C < (1ll << 31) &&
           (int64_t)L2 * 27 < (1ll << 31)))
         return ESP_OK;
-    constexpr int PIX = 8;
-    const int cgroups = (L2 + kWave - 1) / kWave;
-    const int64_t tasks = (int64_t)B * H2 * cgroups;
+    // channel groups of up to 128 (4 MFMA column blocks); one or three blocks only when L2 is
+    // that small, so that a group always starts on a word boundary
+    const int nb = L2 <= 32 ? 1 : (L2 <= 64 ? 2 : 4);
+    const int cgroups = (L2 + nb * 32 - 1) / (nb * 32);
+    const int strips = (W2 + 31) / 32;
+    const int64_t rows_strips = (int64_t)B * H2 * strips;
+    const int64_t tasks = rows_strips * cgroups;
     if (tasks >= (1ll << 31))
         return ESP_OK;
     *done = true;
-    if (bits)
-        hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX, true>), dim3(grid_for(tasks, 4)),
-                           dim3(256), 0, stream, in, filt, out, thr, sgn, bits, H, W, L2, pad, H2, W2,
-                           cgroups, (int)tasks);
-    else
-        hipLaunchKernelGGL((conv_f32_lane_channel_kernel<3, 3, 3, PIX, false>), dim3(grid_for(tasks, 4)),
-                           dim3(256), 0, stream, in, filt, out, thr, sgn, bits, H, W, L2, pad, H2, W2,
-                           cgroups, (int)tasks);
+    // two waves per SIMD stay resident and walk the tasks, so the weights are fetched once per wave
+    const int64_t waves = tasks < 2048 ? tasks : 2048;
+    const dim3 grid((unsigned)ceil_div(waves, 4));
+#define ESP_CONV1(NB, FUSE)                                                                            \
+    hipLaunchKernelGGL((conv3x3x3_mfma_kernel<NB, FUSE>), grid, dim3(256), 0, stream, in, filt, out, thr, \
+                       sgn, bits, H, W, L2, pad, H2, W2, strips, (int)rows_strips, (int)tasks)
+    if (bits) {
+        if (nb == 1)
+            ESP_CONV1(1, true);
+        else if (nb == 2)
+            ESP_CONV1(2, true);
+        else
+            ESP_CONV1(4, true);
+    } else {
+        if (nb == 1)
+            ESP_CONV1(1, false);
+        else if (nb == 2)
+            ESP_CONV1(2, false);
+        else
+            ESP_CONV1(4, false);
+    }
+#undef ESP_CONV1
     return launch_status();
 }
 

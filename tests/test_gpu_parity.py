@@ -454,8 +454,15 @@ def test_dense_f32(M, N, K):
     _assert_close_1e4(got, oracle.dense_f64(x, w))
 
 
+# 3x3x3 stride-1 shapes take the matrix-core kernel: one to four 32-channel blocks, several
+# channel groups, strips of 32 pixels with a ragged last strip, pad 0, 1 and 2
+CONV3_CASES = [(2, 40, 70, 3, 200, 3, 1, 1), (1, 5, 5, 3, 32, 3, 1, 0), (2, 6, 6, 3, 48, 3, 1, 2),
+               (3, 4, 33, 3, 129, 3, 1, 1), (5, 32, 32, 3, 128, 3, 1, 1), (1, 3, 3, 3, 7, 3, 1, 0)]
+
+
 @pytest.mark.parametrize("B,H,W,C,L2,k,stride,pad", [(1, 32, 32, 3, 128, 3, 1, 1), (3, 9, 7, 3, 20, 3, 2, 1),
-                                                     (2, 8, 8, 5, 300, 3, 1, 0), (2, 6, 6, 16, 2000, 3, 1, 1)])
+                                                     (2, 8, 8, 5, 300, 3, 1, 0), (2, 6, 6, 16, 2000, 3, 1, 1)]
+                         + CONV3_CASES)
 def test_conv_f32(B, H, W, C, L2, k, stride, pad):
     rng = np.random.default_rng(B + H + L2)
     x = rng.random((B, H, W, C), dtype=np.float32)
@@ -492,7 +499,7 @@ def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
 def test_conv_f32_bn_sign_pack_fused_equals_two_step():
     rng = np.random.default_rng(4)
     for (B, H, W, C, L2, k, stride, pad) in [(3, 32, 32, 3, 128, 3, 1, 1), (2, 9, 11, 3, 70, 3, 1, 1),
-                                             (2, 8, 8, 5, 40, 3, 1, 0), (1, 7, 7, 3, 64, 3, 2, 1)]:
+                                             (2, 8, 8, 5, 40, 3, 1, 0), (1, 7, 7, 3, 64, 3, 2, 1)] + CONV3_CASES:
         x = rng.random((B, H, W, C), dtype=np.float32)
         f = _pm1(rng, (L2, k, k, C))
         bnp = synth.bn_params(rng, L2)
