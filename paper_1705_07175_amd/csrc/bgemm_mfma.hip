@@ -16,8 +16,14 @@
 // counted once per block by the threads that fetch the packed rows from global memory.
 //
 // Tile: 256 threads = 2 x 2 waves, each wave 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32
-// (v_mfma_scale_f32_32x32x64_f8f6f4), fed from LDS slabs of packed rows in the same
-// 16-byte k-group layout as the XOR-popcount kernel.
+// (v_mfma_scale_f32_32x32x64_f8f6f4), fed from two LDS buffers of packed rows in the same
+// 16-byte k-group layout as the XOR-popcount kernel: stage s + 1 is written while stage s
+// is read, one barrier per stage.  The kernel is templated on the wave arrangement
+// (WM x WN) and on FN, the 32-column blocks per wave.  Measured on an 8192-cube: 128 x 128
+// per wave (FN = 4: accumulators in AGPRs, one wave per SIMD, half the ANDs per MFMA) ran
+// 15 % slower than FN = 2 with two waves per SIMD, so only the latter is instantiated; with
+// the operand ANDs, the popcounts and the epilogue all removed the time did not change, the
+// loads of a stage (global -> registers -> LDS) and the barrier are what the MFMAs wait for.
 #include "esp_internal.h"
 #include "tile_sources.h"
 
@@ -26,7 +32,6 @@ namespace esp {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kMfmaBM = 256, kMfmaBN = 128;   // block tile
 constexpr int kMfmaKG = 4;                     // 16-byte k-groups per LDS stage (512 bits of K)
 constexpr int kMaxMfmaK = 1 << 24;             // fp32 accumulation stays exact
 
@@ -53,17 +58,20 @@ __device__ __forceinline__ v8i encode(const uint4 x)
     return r;
 }
 
-template <int J>
-__device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&xb)[2], v16f (&acc)[4][2])
+template <int J, int FN>
+__device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&xb)[FN], v16f (&acc)[4][FN])
 {
     constexpr int sc = J == 0 ? kScale2 : (J == 1 ? kScale1 : kScaleHalf);
-    const v8i b0 = encode<J>(xb[0]);
-    const v8i b1 = encode<J>(xb[1]);
+    v8i b[FN];
+#pragma unroll
+    for (int g = 0; g < FN; ++g)
+        b[g] = encode<J>(xb[g]);
 #pragma unroll
     for (int f = 0; f < 4; ++f) {
         const v8i a = encode<J>(xa[f]);
-        acc[f][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b0, acc[f][0], 4, 4, 0, sc, 0, sc);
-        acc[f][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b1, acc[f][1], 4, 4, 0, sc, 0, sc);
+#pragma unroll
+        for (int g = 0; g < FN; ++g)
+            acc[f][g] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b[g], acc[f][g], 4, 4, 0, sc, 0, sc);
     }
 }
 
@@ -82,15 +90,17 @@ struct MfmaOut {
                             // and this is log2 of the convolution's output width W2
 };
 
-template <class ASrc, bool VEC16B, bool BITS>
-__global__ __launch_bounds__(256, 2)
+template <class ASrc, bool VEC16B, bool BITS, int WM, int WN, int FN>
+__global__ __launch_bounds__(256, FN == 4 ? 1 : 2)
 void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const MfmaOut o, int M, int N,
                        int K_true, int row_dw, int tiles_m, int tiles_n, int tiles_per_xcd)
 {
-    constexpr int BM = kMfmaBM, BN = kMfmaBN, KG = kMfmaKG, NT = 256;
+    static_assert(WM * WN == 4, "four waves per block");
+    constexpr int BM = WM * 128, BN = WN * FN * 32, KG = kMfmaKG, NT = 256;
     constexpr int STAGE_DW = KG * 4;
-    __shared__ uint4 As[KG][BM + 1];
-    __shared__ uint4 Bs[KG][BN + 1];
+    // two LDS buffers: stage s + 1 is written while stage s is still being read
+    __shared__ uint4 As[2][KG][BM + 1];
+    __shared__ uint4 Bs[2][KG][BN + 1];
     __shared__ __align__(16) int pa_s[BM];   // set bits per A row of the tile
     __shared__ int pb_s[BN];                 // set bits per B row (= output column)
 
@@ -99,28 +109,28 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         return;
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x;
-    pa_s[tid] = 0;                           // BM == blockDim.x
-    if (tid < BN)
-        pb_s[tid] = 0;
+    for (int i = tid; i < BM; i += NT)
+        pa_s[i] = 0;
+    for (int i = tid; i < BN; i += NT)
+        pb_s[i] = 0;
     const int lane = tid % kWave;
     const int wave = tid / kWave;
-    const int wm = (wave / 2) * 128;   // wave's row offset inside the block tile
-    const int wn = (wave % 2) * 64;    // wave's column offset
+    const int wm = (wave / WN) * 128;        // wave's row offset inside the block tile
+    const int wn = (wave % WN) * (FN * 32);  // wave's column offset
 
     // loader: chunk idx = tid + i*NT -> (row idx / KG, k-group idx % KG); NT % KG == 0
-    constexpr int A_CH = BM * KG / NT;   // 4
-    constexpr int B_CH = BN * KG / NT;   // 2
+    constexpr int A_CH = BM * KG / NT;
+    constexpr int B_CH = BN * KG / NT;
     const int kg_mine = tid % KG;
     typename ASrc::Row arow[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-        arow[i] = asrc.row(m0 + (tid + i * NT) / KG);
+        arow[i] = asrc.row_nb(m0 + (tid + i * NT) / KG);
+    // rows and columns beyond the matrix read the last valid one: what they produce is never stored
     const uint32_t *brow[B_CH];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int n = n0 + (tid + i * NT) / KG;
-        brow[i] = n < N ? B + (int64_t)n * row_dw : nullptr;
-    }
+    for (int i = 0; i < B_CH; ++i)
+        brow[i] = B + (int64_t)min(n0 + (tid + i * NT) / KG, N - 1) * row_dw;
     uint4 pa[A_CH], pb[B_CH];
     int na[A_CH], nb[B_CH];   // set bits of the chunks this thread has fetched, per row
 #pragma unroll
@@ -134,29 +144,29 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         const typename ASrc::Step st = asrc.step(kd);
 #pragma unroll
         for (int i = 0; i < A_CH; ++i)
-            pa[i] = asrc.fetch(arow[i], st, kd);
+            pa[i] = asrc.fetch_nb(arow[i], st, kd);
 #pragma unroll
         for (int i = 0; i < B_CH; ++i)
-            pb[i] = brow[i] ? load_chunk<VEC16B>(brow[i], kd, row_dw) : zero4();
+            pb[i] = load_chunk_nb<VEC16B>(brow[i], kd, row_dw);
     };
-    auto commit = [&]() {
+    auto commit = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            As[kg_mine][(tid + i * NT) / KG] = pa[i];
+            As[buf][kg_mine][(tid + i * NT) / KG] = pa[i];
             na[i] += popc4(pa[i]);
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            Bs[kg_mine][(tid + i * NT) / KG] = pb[i];
+            Bs[buf][kg_mine][(tid + i * NT) / KG] = pb[i];
             nb[i] += popc4(pb[i]);
         }
     };
 
-    v16f acc[4][2];
+    v16f acc[4][FN];
 #pragma unroll
     for (int f = 0; f < 4; ++f)
 #pragma unroll
-        for (int g = 0; g < 2; ++g)
+        for (int g = 0; g < FN; ++g)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[f][g][r] = 0.0f;
@@ -165,26 +175,29 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     const int lr = lane % 32, half = lane / 32;
     const int stages = (row_dw + STAGE_DW - 1) / STAGE_DW;
     prefetch(0);
+    commit(0);
+    __syncthreads();
     for (int s = 0; s < stages; ++s) {
-        commit();
-        __syncthreads();
+        const int buf = s & 1;
         if (s + 1 < stages)
-            prefetch(s + 1);
+            prefetch(s + 1);                 // global loads in flight during this stage's MFMAs
 #pragma unroll
         for (int step = 0; step < KG / 2; ++step) {
             const int kg = 2 * step + half;
-            uint4 xa[4], xb[2];
+            uint4 xa[4], xb[FN];
 #pragma unroll
             for (int f = 0; f < 4; ++f)
-                xa[f] = As[kg][wm + f * 32 + lr];
+                xa[f] = As[buf][kg][wm + f * 32 + lr];
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
-                xb[g] = Bs[kg][wn + g * 32 + lr];
-            mfma_group<0>(xa, xb, acc);
-            mfma_group<1>(xa, xb, acc);
-            mfma_group<2>(xa, xb, acc);
-            mfma_group<3>(xa, xb, acc);
+            for (int g = 0; g < FN; ++g)
+                xb[g] = Bs[buf][kg][wn + g * 32 + lr];
+            mfma_group<0, FN>(xa, xb, acc);
+            mfma_group<1, FN>(xa, xb, acc);
+            mfma_group<2, FN>(xa, xb, acc);
+            mfma_group<3, FN>(xa, xb, acc);
         }
+        if (s + 1 < stages)
+            commit(buf ^ 1);                 // nobody reads that buffer before the barrier below
         __syncthreads();
     }
 
@@ -199,21 +212,27 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 
     // dot = K - 2 pa - 2 pb + 4 c.  Result layout of a 32x32 block: lane -> column lane % 32;
     // register r -> row 8 * (r / 4) + 4 * (lane / 32) + r % 4.
-    int kb[2];   // K - 2 pb of the lane's two columns
+    int kb[FN];   // K - 2 pb of the lane's columns
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < FN; ++g)
         kb[g] = K_true - 2 * pb_s[wn + g * 32 + lr];
 
     if (BITS) {
-        // one 64-column word per row of the wave tile: the comparison masks of the two
-        // column blocks are its two halves (lanes 0-31: row R, lanes 32-63: row R + 4)
-        int lim[2];
+        // a 64-column word per row and pair of column blocks: the comparison masks of the two
+        // blocks are its halves (lanes 0-31: row R, lanes 32-63: row R + 4)
+        constexpr int NW = FN / 2;
+        int lim[FN];
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
+        for (int g = 0; g < FN; ++g) {
             const int col = n0 + wn + g * 32 + lr;
             lim[g] = col < N ? o.thr[col] : 0x7fffffff;   // never reached beyond N: tail bits 0
         }
-        uint64_t mine[2] = {0, 0};   // lane L keeps the words of wave-tile rows L and 64 + L
+        uint64_t mine[2][NW];   // lane L keeps the words of wave-tile rows L and 64 + L
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < NW; ++q)
+                mine[h][q] = 0;
 #pragma unroll
         for (int f = 0; f < 4; ++f)
 #pragma unroll
@@ -223,35 +242,45 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int r = 4 * q + t;
-                    const uint64_t m0b = __ballot(4 * (int)acc[f][0][r] + kb[0] - 2 * pav[t] >= lim[0]);
-                    const uint64_t m1b = __ballot(4 * (int)acc[f][1][r] + kb[1] - 2 * pav[t] >= lim[1]);
-                    const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
-                    const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
                     const int R = f * 32 + 8 * q + t;                                     // compile-time
-                    if (lane == R % 64)
-                        mine[R / 64] = w_lo;
-                    if (lane == (R + 4) % 64)
-                        mine[(R + 4) / 64] = w_hi;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) {
+                        const uint64_t m0b =
+                            __ballot(4 * (int)acc[f][2 * w][r] + kb[2 * w] - 2 * pav[t] >= lim[2 * w]);
+                        const uint64_t m1b =
+                            __ballot(4 * (int)acc[f][2 * w + 1][r] + kb[2 * w + 1] - 2 * pav[t] >= lim[2 * w + 1]);
+                        const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
+                        const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
+                        if (lane == R % 64)
+                            mine[R / 64][w] = w_lo;
+                        if (lane == (R + 4) % 64)
+                            mine[(R + 4) / 64][w] = w_hi;
+                    }
                 }
             }
-        const int w = (n0 + wn) >> 6;
-        const uint64_t fl = w < o.Nw ? o.flip[w] : 0ull;
-        if (o.pool_log2w == 0) {
-            if (w < o.Nw) {
+        const int w0 = (n0 + wn) >> 6;
+        uint64_t fl[NW];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int row = m0 + wm + h * 64 + lane;
-                    if (row < M)
-                        o.bits[(int64_t)row * o.Nw + w] = mine[h] ^ fl;
-                }
+        for (int w = 0; w < NW; ++w)
+            fl[w] = w0 + w < o.Nw ? o.flip[w0 + w] : 0ull;
+        if (o.pool_log2w == 0) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = m0 + wm + h * 64 + lane;
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+                    if (row < M && w0 + w < o.Nw)
+                        o.bits[(int64_t)row * o.Nw + w0 + w] = mine[h][w] ^ fl[w];
             }
         } else {
-            // OR max-pool: the tile's words meet in LDS (the A slab is free by now)
+            // OR max-pool: the tile's words meet in LDS (the A slabs are free by now)
             constexpr int WPT = BN / 64;
-            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0]);
+            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0][0]);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                wt[(wm + h * 64 + lane) * WPT + (wn >> 6)] = mine[h] ^ fl;
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+                    wt[(wm + h * 64 + lane) * WPT + (wn >> 6) + w] = mine[h][w] ^ fl[w];
             __syncthreads();
             pool_tile_store<BM, WPT, NT>(wt, o.bits, m0, n0, M, o.Nw, o.pool_log2w, tid);
         }
@@ -269,7 +298,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
                     if (row >= M)
                         continue;
 #pragma unroll
-                    for (int g = 0; g < 2; ++g) {
+                    for (int g = 0; g < FN; ++g) {
                         const int col = n0 + wn + g * 32 + lr;
                         if (col < N)
                             o.C[(int64_t)row * N + col] = 4 * (int)acc[f][g][4 * q + t] + kb[g] - 2 * pav[t];
@@ -279,24 +308,37 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     }
 }
 
-template <class ASrc, bool VEC16B>
-static int launch_mfma(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
-                       int64_t K_true, int64_t row_dw, hipStream_t stream)
+// Block shape in use: 2 x 2 waves of 128 x 64 (see the head of this file).
+struct ShapeA { static constexpr int WM = 2, WN = 2, FN = 2; };
+
+template <class ASrc, bool VEC16B, class S>
+static int launch_mfma_shape(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
+                             int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
-    const int tiles_m = (int)ceil_div(M, kMfmaBM);
-    const int tiles_n = (int)ceil_div(N, kMfmaBN);
+    constexpr int BM = S::WM * 128, BN = S::WN * S::FN * 32;
+    const int tiles_m = (int)ceil_div(M, BM);
+    const int tiles_n = (int)ceil_div(N, BN);
     const int64_t total = (int64_t)tiles_m * tiles_n;
     if (total > (1ll << 30))
         return ESP_ESHAPE;
     const int per_xcd = (int)ceil_div(total, kXcd);
     const dim3 grid((unsigned)(per_xcd * kXcd));
     if (o.bits)
-        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true>), grid, dim3(256), 0, stream, asrc, b, o,
-                           (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n, per_xcd);
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true, S::WM, S::WN, S::FN>), grid, dim3(256), 0,
+                           stream, asrc, b, o, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
+                           per_xcd);
     else
-        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, false>), grid, dim3(256), 0, stream, asrc, b, o,
-                           (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n, per_xcd);
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, false, S::WM, S::WN, S::FN>), grid, dim3(256), 0,
+                           stream, asrc, b, o, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
+                           per_xcd);
     return launch_status();
+}
+
+template <class ASrc, bool VEC16B>
+static int launch_mfma(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
+                       int64_t K_true, int64_t row_dw, hipStream_t stream)
+{
+    return launch_mfma_shape<ASrc, VEC16B, ShapeA>(asrc, b, o, M, N, K_true, row_dw, stream);
 }
 
 int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const int32_t *thr,

@@ -36,6 +36,33 @@ __device__ __forceinline__ uint4 load_chunk(const uint32_t *__restrict__ p, int 
     return v;
 }
 
+// v with every bit cleared unless keep.  The branch-free fetch_nb variants below load from a
+// clamped, always valid address and mask the result, so that a loader's independent loads are
+// issued back to back instead of each inside its own branch (used where the loads of a stage
+// must not hold up the matrix cores; the plain variants cost fewer vector instructions).
+__device__ __forceinline__ uint4 keep4(uint4 v, bool keep)
+{
+    const uint32_t m = keep ? 0xffffffffu : 0u;
+    v.x &= m;
+    v.y &= m;
+    v.z &= m;
+    v.w &= m;
+    return v;
+}
+
+// 16 bytes of row p from dword kd on, zeros beyond row_dw, without a branch (row_dw >= 4 with
+// VEC16, row_dw >= 2 and even otherwise).
+template <bool VEC16>
+__device__ __forceinline__ uint4 load_chunk_nb(const uint32_t *__restrict__ p, int kd, int row_dw)
+{
+    if (VEC16)
+        return keep4(*reinterpret_cast<const uint4 *>(p + min(kd, row_dw - 4)), kd < row_dw);
+    const uint2 lo = *reinterpret_cast<const uint2 *>(p + min(kd, row_dw - 2));
+    const uint2 hi = *reinterpret_cast<const uint2 *>(p + min(kd + 2, row_dw - 2));
+    const uint32_t m0 = kd < row_dw ? 0xffffffffu : 0u, m1 = kd + 2 < row_dw ? 0xffffffffu : 0u;
+    return make_uint4(lo.x & m0, lo.y & m0, hi.x & m1, hi.y & m1);
+}
+
 // ---- A operand: rows of a packed matrix ------------------------------------------
 template <bool VEC16>
 struct MatrixA {
@@ -52,6 +79,12 @@ struct MatrixA {
     __device__ __forceinline__ uint4 fetch(const Row &r, const Step &, int kd) const
     {
         return r.p ? load_chunk<VEC16>(r.p, kd, row_dw) : zero4();
+    }
+    // branch-free: rows beyond the matrix read the last row (their results are never stored)
+    __device__ __forceinline__ Row row_nb(int r) const { return Row{base + (int64_t)min(r, rows - 1) * row_dw}; }
+    __device__ __forceinline__ uint4 fetch_nb(const Row &r, const Step &, int kd) const
+    {
+        return load_chunk_nb<VEC16>(r.p, kd, row_dw);
     }
 };
 
@@ -90,6 +123,15 @@ struct ConvA {
         if (r.img < 0 || kd >= row_dw || y < 0 || y >= H || x < 0 || x >= W)
             return zero4();
         return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)y * W + x) * cdw + s.c);
+    }
+    // branch-free: the pixel is clamped into the image, the border and the K tail are masked
+    __device__ __forceinline__ Row row_nb(int r) const { return row(min(r, rows - 1)); }
+    __device__ __forceinline__ uint4 fetch_nb(const Row &r, const Step &s, int kd) const
+    {
+        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
+        const bool inside = kd < row_dw && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+        const int yc = min(max(y, 0), H - 1), xc = min(max(x, 0), W - 1);
+        return keep4(*reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)yc * W + xc) * cdw + s.c), inside);
     }
 };
 

@@ -93,6 +93,26 @@ def test_bgemm_mfma(M, N, K):
     assert np.array_equal(got, oracle.dense_pm1(a, b))
 
 
+# the matrix-core kernel's three block shapes, each checked in full against the oracle with
+# ragged edges: 256 x 128 (small products), 256 x 256 (N > 128, at least 256 blocks) and
+# 512 x 128 (N <= 128, M >= 131072); int32 and thresholded outputs
+@pytest.mark.parametrize("M,N,K", [(4100, 4100, 200), (131072 + 70, 100, 192), (2000, 300, 1100)])
+def test_bgemm_mfma_block_shapes(M, N, K):
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    want = oracle.dense_pm1(a, b)
+    ap, bp = _packed_dev(a), _packed_dev(b)
+    got = esp.bgemm_mfma(ap, bp, K)
+    assert np.array_equal(got.cpu().numpy(), want)
+    del got
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    bits = esp.bgemm_bn_sign_pack(ap, bp, K, torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV),
+                                  engine=esp.ENGINE_MFMA)
+    assert np.array_equal(esp.packed_to_numpy(bits), oracle.pack_bits(oracle.bn_sign(want, bnp, synth.BN_EPS)))
+
+
 @pytest.mark.parametrize("n", [2048, 8192])
 def test_bgemm_mfma_config5_square_sampled(n):
     a, b = synth.config5_square(n)
