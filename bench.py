@@ -355,6 +355,11 @@ def _networks(torch, esp, nets, synth, dev, only=None):
         x8 = (torch.from_numpy(synth.mlp_input(batch)).to(dev) * 256.0).clamp(0, 255).to(torch.uint8)
         res["bmlp"][str(batch) + "_bitplane_first_layer"] = time_net(net, x8, batch, 50)
         del net
+        if batch >= 1024:
+            # large batches: let the library put the binary layers on the matrix cores
+            net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev, engine=esp.ENGINE_AUTO)
+            res["bmlp"][str(batch) + "_auto_engine"] = time_net(net, x, batch, 50)
+            del net
     layers = synth.cnn_params()
     for batch in (1, 256):
         if only and only != ("bcnn", batch):

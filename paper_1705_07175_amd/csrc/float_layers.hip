@@ -1,64 +1,127 @@
 // Real-valued first layer in fp32 (the non-binary variant of a layer, Sec. 3 of
 // arXiv 1705.07175): the networks of Sec. 6.2 / 6.3 start from real-valued images, so
 // their first dense / convolutional layer multiplies floats by +-1 weights.  These are
-// supporting kernels: an LDS-tiled SGEMM, a wave-per-output GEMV for tiny batches, a
-// direct convolution with the filters transposed in LDS for general shapes, and the 3x3x3
-// first layer of the CIFAR-10 network on the fp32 matrix cores.
+// supporting kernels: an LDS-tiled SGEMM on the fp32 matrix cores, a wave-per-output GEMV for
+// tiny batches, a direct convolution with the filters transposed in LDS for general shapes,
+// and the 3x3x3 first layer of the CIFAR-10 network, again on the fp32 matrix cores.
 #include "esp_internal.h"
 
 namespace esp {
 
-// Y[M][N] = X[M][K] * W[N][K]^T, 64x64 tile, 256 threads, 4x4 outputs per thread.
+// Y[M][N] = X[M][K] * W[N][K]^T on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): 64 x BN
+// block tile, 256 threads = 4 waves, K in slabs of 32 staged in LDS k-major, so that lane
+// (row or column lane % 32, k half lane / 32) reads its A and B operand of a k-step with one
+// conflict-free 4-byte LDS read each.  BN = 64: 2 x 2 waves of 32 x 32.  BN = 32 (small
+// batches: twice the blocks): 2 x 1 waves of 32 x 32, the two wave pairs take alternate
+// k-steps and their partial sums meet in LDS at the end.  The next slab is fetched into
+// registers (16-byte loads when K allows) while the current one is multiplied, so a block
+// pays the memory latency once and not once per slab.
+// Result layout of the MFMA: lane -> column lane % 32, register r -> row 8 (r/4) + 4 (lane/32) + r%4.
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int BN, bool VEC4>
 __global__ __launch_bounds__(256)
-void dense_f32_tile_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
+void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
                            float *__restrict__ Y, int M, int N, int K)
 {
-    constexpr int BT = 64, BK = 16;
-    __shared__ float Xs[BK][BT + 4];
-    __shared__ float Ws[BK][BT + 4];
+    constexpr int BM = 64, BK = 32;
+    constexpr int XQ = BM * BK / 4 / 256;   // float4 units per thread and slab: 2
+    constexpr int WQ = BN * BK / 4 / 256;   // 2 (BN = 64) or 1 (BN = 32)
+    __shared__ float Xs[BK][BM + 4];
+    __shared__ float Ws[BK][BN + 4];
     const int tid = threadIdx.x;
-    const int tx = tid % 16, ty = tid / 16;
-    const int m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += BK) {
-        // 64 rows x 16 k per operand = 1024 values, 4 per thread; k fastest so that a
-        // group of 16 lanes reads 64 contiguous bytes of one row
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + i * 256;
-            const int r = idx / BK, k = idx % BK;
-            const bool kin = k0 + k < K;
-            Xs[k][r] = (kin && m0 + r < M) ? X[(int64_t)(m0 + r) * K + k0 + k] : 0.0f;
-            Ws[k][r] = (kin && n0 + r < N) ? Wt[(int64_t)(n0 + r) * K + k0 + k] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < BK; ++k) {
-            float a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = Xs[k][ty + 16 * i];
-                b[i] = Ws[k][tx + 16 * i];
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    // unit u = tid + i * 256 -> row u / 8, k offset 4 * (u % 8): 8 lanes read 128 contiguous bytes
+    float4 xr[XQ], wr[WQ];
+    auto fetch = [&](const float *base, int row, int rows, int k0, int u) {
+        const int r = row + u / 8, k = k0 + 4 * (u % 8);
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (r < rows) {
+            const float *p = base + (int64_t)r * K + k;
+            if (VEC4) {
+                if (k < K)
+                    v = *reinterpret_cast<const float4 *>(p);   // K % 4 == 0: whole or nothing
+            } else {
+                if (k + 0 < K) v.x = p[0];
+                if (k + 1 < K) v.y = p[1];
+                if (k + 2 < K) v.z = p[2];
+                if (k + 3 < K) v.w = p[3];
             }
+        }
+        return v;
+    };
+    auto prefetch = [&](int k0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < XQ; ++i)
+            xr[i] = fetch(X, m0, M, k0, tid + i * 256);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        for (int i = 0; i < WQ; ++i)
+            wr[i] = fetch(Wt, n0, N, k0, tid + i * 256);
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < XQ; ++i) {
+            const int u = tid + i * 256, r = u / 8, k = 4 * (u % 8);
+            Xs[k + 0][r] = xr[i].x;
+            Xs[k + 1][r] = xr[i].y;
+            Xs[k + 2][r] = xr[i].z;
+            Xs[k + 3][r] = xr[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < WQ; ++i) {
+            const int u = tid + i * 256, r = u / 8, k = 4 * (u % 8);
+            Ws[k + 0][r] = wr[i].x;
+            Ws[k + 1][r] = wr[i].y;
+            Ws[k + 2][r] = wr[i].z;
+            Ws[k + 3][r] = wr[i].w;
+        }
+    };
+
+    const int lane = tid % kWave, wave = tid / kWave;
+    const int lr = lane % 32, half = lane / 32;
+    constexpr int WN = BN / 32;              // waves along N: 2 or 1
+    const int wm = (wave % 2) * 32;          // wave's row offset
+    const int wn = WN == 2 ? (wave / 2) * 32 : 0;
+    const int kpart = WN == 2 ? 0 : wave / 2;   // BN = 32: which of the alternate k-steps
+    v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        acc[r] = 0.0f;
+    prefetch(0);
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        commit();
+        __syncthreads();
+        if (k0 + BK < K)
+            prefetch(k0 + BK);
+#pragma unroll
+        for (int st = 0; st < BK / 2 / (3 - WN); ++st) {
+            const int k = 2 * (WN == 2 ? st : 2 * st + kpart) + half;
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Xs[k][wm + lr], Ws[k][wn + lr], acc, 0, 0, 0);
         }
         __syncthreads();
     }
+    if (WN == 1) {
+        // the wave pairs 0,1 and 2,3 hold partial sums of the same 64 x 32 tile
+        float *red = &Xs[0][0];              // 32 x 68 floats >= 2 waves x 16 x 64
+        if (wave >= 2) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty + 16 * i;
-        if (m >= M)
-            continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + tx + 16 * j;
-            if (n < N)
-                Y[(int64_t)m * N + n] = acc[i][j];
+            for (int r = 0; r < 16; ++r)
+                red[((wave - 2) * 16 + r) * kWave + lane] = acc[r];
         }
+        __syncthreads();
+        if (wave >= 2)
+            return;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            acc[r] += red[(wave * 16 + r) * kWave + lane];
+    }
+    const int n = n0 + wn + lr;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm + 8 * (r / 4) + 4 * half + r % 4;
+        if (m < M && n < N)
+            Y[(int64_t)m * N + n] = acc[r];
     }
 }
 
@@ -157,7 +220,6 @@ void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ fil
 //    bits of two pixels x 32 channels; only packed words leave the kernel (the pre-
 //    activations are written as well only if `pre` is given).
 // MFMA result layout: lane -> column lane % 32, register r -> row 8 (r / 4) + 4 (lane / 32) + r % 4.
-typedef float v16f __attribute__((ext_vector_type(16)));
 
 // v or +0.0f.  A bit mask instead of a select keeps the load that produced v unconditional
 // (from a clamped, always valid address), so that independent loads are issued back to back
@@ -366,8 +428,20 @@ extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
     const int64_t gy = ceil_div(M, 64);
     if (gy > 65535)
         return ESP_ESHAPE;
-    const dim3 grid((unsigned)ceil_div(N, 64), (unsigned)gy);
-    hipLaunchKernelGGL(dense_f32_tile_kernel, grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K);
+    const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
+    const bool narrow = gy * ceil_div(N, 64) < 256;   // few blocks: halve the tile width
+    const dim3 grid((unsigned)ceil_div(N, narrow ? 32 : 64), (unsigned)gy);
+#define ESP_DENSE(BN, V) \
+    hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K)
+    if (narrow && vec4)
+        ESP_DENSE(32, true);
+    else if (narrow)
+        ESP_DENSE(32, false);
+    else if (vec4)
+        ESP_DENSE(64, true);
+    else
+        ESP_DENSE(64, false);
+#undef ESP_DENSE
     return launch_status();
 }
 

@@ -465,7 +465,8 @@ def _assert_close_1e4(got, ref):
     assert np.all(err <= tol), float((err / tol).max())
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (3, 100, 50), (64, 4096, 784), (70, 130, 97), (4, 10, 784)])
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (3, 100, 50), (64, 4096, 784), (70, 130, 97), (4, 10, 784),
+                                   (1024, 4096, 784), (300, 1000, 130), (65, 33, 36), (5, 64, 31), (2000, 700, 100)])
 def test_dense_f32(M, N, K):
     rng = np.random.default_rng(M + N + K)
     x = rng.random((M, K), dtype=np.float32)
