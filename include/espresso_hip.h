@@ -272,12 +272,21 @@ int esp_conv_f32(const float *in, const float *filt, float *out,
 /* (float [B][H2][W2][L2], the pre-activations) only if not NULL.  For filter */
 /* shapes without a fused kernel `pre` is required as scratch                 */
 /* (ESP_EWORKSPACE if NULL).                                                  */
+/*                                                                            */
+/* dense_f32_bn_sign_pack: esp_dense_f32 followed by esp_bn_sign_pack_f32;    */
+/* `bits` uint64 [M][ceil(N/64)] is always written, `pre` (float [M][N]) only */
+/* if not NULL.  Up to M = 4 (one image at a time, Sec. 6.2) this is a single */
+/* kernel; for larger M `pre` is required as scratch (ESP_EWORKSPACE if NULL).*/
 /* ------------------------------------------------------------------------- */
 int esp_bn_fold_f32(const float *gamma, const float *beta, const float *mean, const float *var,
                     float eps, int C, float *thr, float *sgn);
 
 int esp_bn_sign_pack_f32(const float *x, const float *thr, const float *sgn,
                          uint64_t *out, int64_t rows, int C, esp_stream stream);
+
+int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const float *thr, const float *sgn,
+                               uint64_t *bits, float *pre, int64_t M, int64_t N, int64_t K,
+                               esp_stream stream);
 
 int esp_conv_f32_bn_sign_pack(const float *in, const float *filt, const float *thr, const float *sgn,
                               uint64_t *bits, float *pre,

@@ -29,7 +29,7 @@ EXPORTS = (
     "esp_conv_f32_bn_sign_pack", "esp_bconv_needs_workspace", "esp_bgemm_bn_sign_pack",
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
-    "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2"
+    "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2", "esp_dense_f32_bn_sign_pack",
 )
 
 _lib = None
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bgemm_mfma.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         l.esp_bconv_pool2_fusable.argtypes = [i32] * 7
         l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
+        l.esp_dense_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_version.argtypes = []
         for name in EXPORTS:
             # without a prototype ctypes would pass pointers as 32-bit ints: refuse to load
@@ -353,6 +354,25 @@ def dense_f32(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None)
         raise ValueError("K mismatch")
     out = _out(out, (M, N), torch.float32, x.device)
     _check(lib().esp_dense_f32(px, pw, _dev(out, torch.float32, "out"), M, N, K, _stream()), "esp_dense_f32")
+    return out
+
+
+def dense_f32_bn_sign_pack(x: torch.Tensor, w: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
+                           out: torch.Tensor | None = None, pre: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_dense_f32_bn_sign_pack``: float dense layer + folded batch-norm + sign -> packed [M][Nw].
+    ``pre`` (float [M][N]) receives the pre-activations if given; it is required for M > 4."""
+    px, pw = _dev(x, torch.float32, "x"), _dev(w, torch.float32, "w")
+    M, K = x.shape
+    N, K2 = w.shape
+    if K != K2 or thr.numel() != N or sgn.numel() != N:
+        raise ValueError("shape mismatch")
+    out = _out(out, (M, words(N)), PACKED, x.device)
+    if pre is not None:
+        _out(pre, (M, N), torch.float32, x.device)
+    ppre = _dev(pre, torch.float32, "pre") if pre is not None else None
+    _check(lib().esp_dense_f32_bn_sign_pack(px, pw, _dev(thr, torch.float32, "thr"), _dev(sgn, torch.float32, "sgn"),
+                                            _dev(out, PACKED, "out"), ppre, M, N, K, _stream()),
+           "esp_dense_f32_bn_sign_pack")
     return out
 
 

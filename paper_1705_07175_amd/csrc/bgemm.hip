@@ -517,16 +517,17 @@ static int launch_gemv(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t
 
 // ---------------------------------------------------------------------------------
 // Small-M product with the folded batch-norm threshold + sign in the epilogue (one image at
-// a time, Sec. 6.2 "Optimized kernels"): a block owns 64 consecutive rows of B, i.e. exactly
-// one packed output word per row of A, so no int32 score and no second launch is needed.
-// The block's waves split the 64 rows; inside a wave lpr lanes share a row as in
-// bgemv_kernel, and every lane keeps PASSES rows in flight (PASSES = lpr * waves / 64).
+// a time, Sec. 6.2 "Optimized kernels"): a block owns RB = 64 or 16 consecutive rows of B,
+// i.e. one packed output word, or one 16-bit quarter of it, per row of A, so no int32 score
+// and no second launch is needed (16 rows when 64 would leave most CUs without a block).
+// The block's waves split the rows; inside a wave lpr lanes share a row as in bgemv_kernel,
+// and every lane keeps PASSES rows in flight (waves * PASSES * 64 / lpr == RB).
 // ---------------------------------------------------------------------------------
 template <int MS, bool VEC16, int PASSES>
 __global__ __launch_bounds__(1024)
 void bgemv_bits_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B,
                        const int32_t *__restrict__ thr, const uint64_t *__restrict__ flip,
-                       uint64_t *__restrict__ out, int M, int N, int K_true, int row_words, int lpr)
+                       uint64_t *__restrict__ out, int M, int N, int K_true, int row_words, int lpr, int RB)
 {
     using CK = Chunk<VEC16>;
     using chunk_t = typename CK::type;
@@ -543,7 +544,7 @@ void bgemv_bits_kernel(const uint64_t *__restrict__ A, const uint64_t *__restric
     const int rpw = kWave / lpr;          // rows of B per wave pass
     const int sub = lane / lpr;
     const int cl = lane % lpr;
-    const int n_blk = blockIdx.x * 64;
+    const int n_blk = blockIdx.x * RB;
     // row handled in pass p: the wave owns PASSES * rpw consecutive rows
     const int row0 = n_blk + wave * (PASSES * rpw) + sub;
 
@@ -603,9 +604,16 @@ void bgemv_bits_kernel(const uint64_t *__restrict__ A, const uint64_t *__restric
     }
     __syncthreads();
     for (int m = wave; m < M; m += blockDim.x / kWave) {
-        const uint64_t word = __ballot(decided[m][lane] != 0);
-        if (lane == 0)
+        const uint64_t word = __ballot(lane < RB && decided[m][lane] != 0);
+        if (lane != 0)
+            continue;
+        if (RB == 64) {
             out[(int64_t)m * gridDim.x + blockIdx.x] = word ^ flip[blockIdx.x];
+        } else {
+            // quarter blockIdx.x % 4 of word blockIdx.x / 4 (little-endian: 16-bit piece j = bits 16 j ..)
+            const uint64_t fl = flip[blockIdx.x / 4] >> (16 * (blockIdx.x % 4));
+            reinterpret_cast<uint16_t *>(out)[(int64_t)m * gridDim.x + blockIdx.x] = (uint16_t)(word ^ fl);
+        }
     }
 }
 
@@ -618,14 +626,20 @@ static int launch_gemv_bits2(const uint64_t *A, const uint64_t *B, const int32_t
     int lpr = 1;
     while (lpr < kWave && lpr < nch)
         lpr <<= 1;
-    // 64 rows per block = waves * PASSES * (64 / lpr): up to 16 waves, then rows in flight per lane
-    const int waves = lpr < 16 ? lpr : 16;
-    const int passes = lpr / waves;   // 1, 2 or 4
-    const dim3 grid((unsigned)ceil_div(N, 64)), block((unsigned)(waves * kWave));
+    // RB rows per block = waves * PASSES * (64 / lpr).  64 rows (up to 16 waves) when that still
+    // gives every CU a block or the rows are too short to split further, else 16 (up to 4 waves);
+    // the grid covers every 16-bit piece of the output words, also those beyond N (zeros)
+    const int64_t Nw = ceil_div(N, 64);
+    const int RB = (Nw >= 256 || lpr < 4) ? 64 : 16;
+    const int total = RB * lpr / 64;
+    const int maxw = RB == 64 ? 16 : 4;
+    const int waves = total < maxw ? total : maxw;
+    const int passes = total / waves;   // 1, 2 or 4
+    const dim3 grid((unsigned)(RB == 64 ? Nw : 4 * Nw)), block((unsigned)(waves * kWave));
     const size_t lds = (size_t)MS * row_words * 8;
 #define ESP_GEMV_BITS(P)                                                                                 \
     hipLaunchKernelGGL((bgemv_bits_kernel<MS, VEC16, P>), grid, block, lds, stream, A, B, thr, flip, out, \
-                       (int)M, (int)N, (int)K_true, (int)row_words, lpr)
+                       (int)M, (int)N, (int)K_true, (int)row_words, lpr, RB)
     if (passes == 1)
         ESP_GEMV_BITS(1);
     else if (passes == 2)

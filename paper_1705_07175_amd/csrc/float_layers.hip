@@ -158,6 +158,101 @@ void dense_f32_gemv_kernel(const float *__restrict__ X, const float *__restrict_
     }
 }
 
+// Small batch with the folded batch-norm threshold + sign in the epilogue (the network of
+// Sec. 6.2 evaluated one image at a time): a block of WAVES waves owns 4 * WAVES = 64 or 16
+// consecutive neurons, i.e. one packed output word, or one 16-bit quarter of it, per row of
+// X (16 when 64 would leave most CUs without a block); every wave streams the weight rows
+// of 4 neurons (all four in flight together), the lanes stride over K, a butterfly sums.
+// bit n of row m = (sgn[n] * y[m][n] >= thr[n]); pre (if not null) also receives y.
+template <int MS, bool VEC4, int WAVES>
+__global__ __launch_bounds__(WAVES * 64)
+void dense_f32_gemv_bits_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
+                                const float *__restrict__ thr, const float *__restrict__ sgn,
+                                uint64_t *__restrict__ bits, float *__restrict__ pre, int M, int N, int K)
+{
+    constexpr int NPW = 4;                       // neurons per wave
+    constexpr int RB = NPW * WAVES;              // neurons per block: 64 or 16
+    __shared__ unsigned char decided[MS][RB];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int n_blk = blockIdx.x * RB;
+    const int nl0 = wave * NPW;
+    float acc[NPW][MS];
+#pragma unroll
+    for (int j = 0; j < NPW; ++j)
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+            acc[j][m] = 0.0f;
+    // rows beyond N read the last row: their results are never used
+    const float *wrow[NPW];
+#pragma unroll
+    for (int j = 0; j < NPW; ++j)
+        wrow[j] = Wt + (int64_t)min(n_blk + nl0 + j, N - 1) * K;
+    if (VEC4) {
+        for (int k = 4 * lane; k < K; k += 4 * kWave) {
+            float4 w[NPW];
+#pragma unroll
+            for (int j = 0; j < NPW; ++j)
+                w[j] = *reinterpret_cast<const float4 *>(wrow[j] + k);
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                if (m >= M)
+                    continue;
+                const float4 x = *reinterpret_cast<const float4 *>(X + (int64_t)m * K + k);
+#pragma unroll
+                for (int j = 0; j < NPW; ++j) {
+                    acc[j][m] = fmaf(x.x, w[j].x, acc[j][m]);
+                    acc[j][m] = fmaf(x.y, w[j].y, acc[j][m]);
+                    acc[j][m] = fmaf(x.z, w[j].z, acc[j][m]);
+                    acc[j][m] = fmaf(x.w, w[j].w, acc[j][m]);
+                }
+            }
+        }
+    } else {
+        for (int k = lane; k < K; k += kWave) {
+            float w[NPW];
+#pragma unroll
+            for (int j = 0; j < NPW; ++j)
+                w[j] = wrow[j][k];
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                if (m >= M)
+                    continue;
+                const float x = X[(int64_t)m * K + k];
+#pragma unroll
+                for (int j = 0; j < NPW; ++j)
+                    acc[j][m] = fmaf(x, w[j], acc[j][m]);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NPW; ++j) {
+        const int n = n_blk + nl0 + j;
+        const int nc = min(n, N - 1);
+        const float t = thr[nc], sg = sgn[nc];
+#pragma unroll
+        for (int m = 0; m < MS; ++m) {
+            float v = acc[j][m];
+            for (int off = 32; off > 0; off >>= 1)
+                v += __shfl_xor(v, off, kWave);
+            if (lane == 0) {
+                decided[m][nl0 + j] = n < N && sg * v >= t;
+                if (pre && n < N && m < M)
+                    pre[(int64_t)m * N + n] = v;
+            }
+        }
+    }
+    __syncthreads();
+    for (int m = wave; m < M; m += WAVES) {
+        const uint64_t word = __ballot(lane < RB && decided[m][lane % RB] != 0);
+        if (lane != 0)
+            continue;
+        if (RB == 64)
+            bits[(int64_t)m * gridDim.x + blockIdx.x] = word;
+        else   // 16-bit piece blockIdx.x % 4 of word blockIdx.x / 4 (little-endian)
+            reinterpret_cast<uint16_t *>(bits)[(int64_t)m * gridDim.x + blockIdx.x] = (uint16_t)word;
+    }
+}
+
 // Direct NHWC convolution, zero padding.  The block copies the filters to LDS as
 // [tap*C + c][L2] so that lanes (= output channels) read consecutive addresses, then
 // walks its share of output pixels; the input value of a tap is the same for every lane
@@ -442,6 +537,61 @@ extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
     else
         ESP_DENSE(64, false);
 #undef ESP_DENSE
+    return launch_status();
+}
+
+extern "C" int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const float *thr, const float *sgn,
+                                          uint64_t *bits, float *pre, int64_t M, int64_t N, int64_t K,
+                                          esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31))
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!X || !W || !thr || !sgn || !bits)
+        return ESP_EINVAL;
+    if (!aligned(X, 4) || !aligned(W, 4) || !aligned(thr, 4) || !aligned(sgn, 4) || !aligned(bits, 8) ||
+        (pre && !aligned(pre, 4)))
+        return ESP_EALIGN;
+    if (M > 4) {
+        // larger batches: the two-kernel route through the pre-activation buffer
+        if (!pre)
+            return ESP_EWORKSPACE;
+        const int st = esp_dense_f32(X, W, pre, M, N, K, stream);
+        if (st != ESP_OK)
+            return st;
+        if (N >= (1ll << 31))
+            return ESP_ESHAPE;
+        return esp_bn_sign_pack_f32(pre, thr, sgn, bits, M, (int)N, stream);
+    }
+    const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
+    // 64 neurons per block when that gives every CU a block, else 16; the grid covers every
+    // 16-bit piece of the output words, also those beyond N (zeros)
+    const int64_t Nw = ceil_div(N, 64);
+    const bool wide = Nw >= 256;
+    const dim3 grid((unsigned)(wide ? Nw : 4 * Nw));
+    hipStream_t s = as_stream(stream);
+#define ESP_GEMV_BITS_F32(MS, V)                                                                           \
+    do {                                                                                                   \
+        if (wide)                                                                                          \
+            hipLaunchKernelGGL((dense_f32_gemv_bits_kernel<MS, V, 16>), grid, dim3(1024), 0, s, X, W, thr, \
+                               sgn, bits, pre, (int)M, (int)N, (int)K);                                    \
+        else                                                                                               \
+            hipLaunchKernelGGL((dense_f32_gemv_bits_kernel<MS, V, 4>), grid, dim3(256), 0, s, X, W, thr,   \
+                               sgn, bits, pre, (int)M, (int)N, (int)K);                                    \
+    } while (0)
+    if (M == 1 && vec4)
+        ESP_GEMV_BITS_F32(1, true);
+    else if (M == 1)
+        ESP_GEMV_BITS_F32(1, false);
+    else if (vec4)
+        ESP_GEMV_BITS_F32(4, true);
+    else
+        ESP_GEMV_BITS_F32(4, false);
+#undef ESP_GEMV_BITS_F32
     return launch_status();
 }
 

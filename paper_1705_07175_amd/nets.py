@@ -45,8 +45,10 @@ class BinaryMLP:
     """Sec. 6.2 network: float dense, then binary dense layers, BN + sign in between."""
 
     def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True,
-                 first_layer: str = "float", engine: int = esp.ENGINE_XOR_POPCOUNT):
+                 first_layer: str = "float", engine: int = esp.ENGINE_XOR_POPCOUNT,
+                 keep_first_pre: bool = False):
         self.batch = batch
+        self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
         self.engine = engine    # units that evaluate the fused binary layers (esp_engine)
         # "float": fp32 first layer on real-valued input; "bitplane": 8-bit input split into
         # bit-planes and run through the binary product (Sec. 4.3, Eq. 3), exact in integers
@@ -79,8 +81,10 @@ class BinaryMLP:
             esp.bitplane_combine(self.plane_dots, self.wsum0, out=self.pre[0])
             esp.bn_sign_pack(self.pre[0], self.bn[0].thr, self.bn[0].flip, out=self.act[0])
         else:
-            esp.dense_f32(x, self.w1, out=self.pre[0])
-            esp.bn_sign_pack_f32(self.pre[0], self.bn[0].thr, self.bn[0].sgn, out=self.act[0])
+            # one kernel up to 4 rows (then pre[0] is written only when asked for), two beyond
+            keep = self.keep_first_pre or self.batch > 4
+            esp.dense_f32_bn_sign_pack(x, self.w1, self.bn[0].thr, self.bn[0].sgn, out=self.act[0],
+                                       pre=self.pre[0] if keep else None)
         self._binary_layers()
         return self.pre[-1]
 

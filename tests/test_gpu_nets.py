@@ -49,7 +49,7 @@ def _check_first_layer(pre_gpu, act_gpu_words, rec, bnp, C):
 def test_mlp_forward(batch):
     layers = synth.mlp_params()
     x = synth.mlp_input(batch)
-    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=False)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=False, keep_first_pre=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     assert scores.shape == (batch, 10) and scores.dtype == np.int32
 
@@ -68,7 +68,7 @@ def test_mlp_forward_fused_small_batch(batch):
     # at most 8 rows: the binary layers run as the small-M product with the threshold epilogue
     layers = synth.mlp_params()
     x = synth.mlp_input(batch)
-    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=True)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, fused=True, keep_first_pre=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     ref = onets.mlp_forward(x, layers, EPS)
     act0 = _check_first_layer(net.pre[0].cpu().numpy(), esp.packed_to_numpy(net.act[0]), ref[0],

@@ -277,7 +277,8 @@ def test_bn_sign_pack(rows, C, K):
 # M <= 8 takes the small-M kernel (64 rows of B per block): every row-split it has (K from one
 # chunk per row to several chunks per lane), odd word counts, ragged N, and M = 1, 2, 4, 8 and between
 SMALL_M_BITS = [(1, 4096, 4096), (2, 100, 70), (3, 1024, 1024), (4, 130, 192), (5, 7, 1000), (8, 1024, 8192),
-                (8, 65, 1), (7, 33, 200), (1, 1000, 65472), (2, 129, 20000), (6, 64, 640), (1, 10, 320)]
+                (8, 65, 1), (7, 33, 200), (1, 1000, 65472), (2, 129, 20000), (6, 64, 640), (1, 10, 320),
+                (1, 16400, 256), (3, 16384, 64), (2, 300, 128)]
 
 
 @pytest.mark.parametrize("engine", [0, 1])
@@ -490,6 +491,30 @@ def test_conv_f32(B, H, W, C, L2, k, stride, pad):
     f = _pm1(rng, (L2, k, k, C))
     got = esp.conv_f32(_f32(x), _f32(f), stride, pad).cpu().numpy()
     _assert_close_1e4(got, oracle.conv_f64(x, f, stride, pad))
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (2, 100, 50), (3, 64, 31), (4, 130, 784), (1, 65, 4),
+                                   (4, 1000, 1001), (5, 4096, 784), (70, 130, 97), (2, 16390, 64)])
+def test_dense_f32_bn_sign_pack(M, N, K):
+    # M <= 4: one kernel (64 neurons per block); beyond: dense + threshold through `pre`
+    rng = np.random.default_rng(M + 10 * N + 100 * K)
+    x = rng.random((M, K), dtype=np.float32)
+    w = _pm1(rng, (N, K))
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K) + 0.5 * w.sum(axis=1)).astype(np.float32), bnp[3])
+    thr, sgn = esp.bn_fold_f32(*bnp, synth.BN_EPS)
+    xd, wd, td, sd = _f32(x), _f32(w), _f32(thr), _f32(sgn)
+    pre = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    bits = esp.dense_f32_bn_sign_pack(xd, wd, td, sd, pre=pre)
+    _assert_close_1e4(pre.cpu().numpy(), oracle.dense_f64(x, w))
+    # bits equal the oracle's batch-norm + sign of those same fp32 pre-activations
+    want = oracle.pack_bits(oracle.bn_sign(pre.cpu().numpy().astype(np.float64), bnp, synth.BN_EPS))
+    assert np.array_equal(esp.packed_to_numpy(bits), want)
+    if M <= 4:
+        assert torch.equal(esp.dense_f32_bn_sign_pack(xd, wd, td, sd), bits)      # without `pre`
+    else:
+        with pytest.raises(esp.EspressoError):
+            esp.dense_f32_bn_sign_pack(xd, wd, td, sd)
 
 
 def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
