@@ -243,6 +243,17 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         for (int j = 0; j < TN; ++j)
             acc[i][j] = 0;
 
+    // thresholds of the lane's columns.  The small tiles serve products whose time is a chain
+    // of memory latencies, so they fetch them now, alongside the first stage; the large tile
+    // keeps its registers for the main loop and fetches them in the epilogue.
+    constexpr bool kEarlyLimits = BITS && TM < 8;
+    int lim[BITS ? TN : 1];
+    if constexpr (kEarlyLimits) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+    }
+
     const int stages = (row_dw + kStageDw - 1) / kStageDw;
     prefetch(0);
     for (int s = 0; s < stages; ++s) {
@@ -277,10 +288,11 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
     // Epilogue: dot = K - 2 * mismatches.
     if constexpr (BITS) {
         static_assert(TX == 16, "a 64-column word is spread over 16 lanes x 4 columns");
-        int lim[TN];
+        if constexpr (!kEarlyLimits) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+            for (int j = 0; j < TN; ++j)
+                lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+        }
         LaneWord lw;
         if constexpr (TM == 8)
             lw = bits.template tile<TY>(acc, lim, tx, ty);

@@ -335,9 +335,9 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
     constexpr int T = 27, KS = 14;                 // taps * channels, k-steps of 2
     constexpr int PIX = 32, WROW = (PIX + 2) * 3;  // floats per window row
     constexpr int WIN = 3 * WROW;
-    constexpr int kSlots = NB < 2 ? 2 : NB;        // 32-bit slots per pixel in the word table
+    static_assert(NB == 1 || NB == 4, "one block per wave (32-bit output pieces) or whole words");
     __shared__ float win_all[4][WIN + 2];          // + a zero slot for the padding k = 27, + scratch
-    __shared__ __align__(16) uint32_t word_all[4][PIX * kSlots];
+    __shared__ __align__(16) uint32_t word_all[4][PIX * NB];   // [pixel][block] mask halves
 
     const int lane = threadIdx.x % kWave;
     // the wave index and everything derived from it (the task decomposition) stay in scalar registers
@@ -464,31 +464,45 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
             // comparison mask of register r, block nb: low half = the 32 channel bits of pixel
             // 8 (r/4) + r%4, high half = those of that pixel + 4.  Lanes 0 and 32 drop the halves
             // into the wave's LDS word table [pixel][block]; lane p then stores pixel p's words.
-            uint32_t *wl = word_all[wave];
+            if constexpr (NB == 1) {
+                // one 32-channel block per wave (small grids): the mask halves are 32-bit pieces
+                // of the output words, stored straight from lanes 0 and 32
+                uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                uint32_t v[NB];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const uint64_t mask = __ballot(acc[nb][r] >= th[nb]);
-                    v[nb] = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+                for (int r = 0; r < 16; ++r) {
+                    const uint64_t mask = __ballot(acc[0][r] >= th[0]);
+                    const uint32_t v = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+                    const int p = 8 * (r / 4) + 4 * half + r % 4;
+                    if (lr == 0 && n0 + p < W2)
+                        bits32[(pix0 + p) * (2 * Cw) + cg] = v;
                 }
-                const int p = 8 * (r / 4) + 4 * half + r % 4;
-                if (lr == 0) {
+            } else {
+                uint32_t *wl = word_all[wave];
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        wl[p * kSlots + nb] = v[nb];
+                for (int r = 0; r < 16; ++r) {
+                    uint32_t v[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const uint64_t mask = __ballot(acc[nb][r] >= th[nb]);
+                        v[nb] = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+                    }
+                    const int p = 8 * (r / 4) + 4 * half + r % 4;
+                    if (lr == 0) {
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            wl[p * NB + nb] = v[nb];
+                    }
                 }
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane < PIX && n0 + lane < W2) {
+                __builtin_amdgcn_wave_barrier();
+                if (lane < PIX && n0 + lane < W2) {
 #pragma unroll
-                for (int q = 0; q < (NB + 1) / 2; ++q) {
-                    const int w = cg * ((NB * 32) / 64) + q;
-                    const uint64_t lo = wl[lane * kSlots + 2 * q];
-                    const uint64_t hi = 2 * q + 1 < NB ? wl[lane * kSlots + 2 * q + 1] : 0u;
-                    if (w < Cw)
-                        bits[(pix0 + lane) * Cw + w] = lo | (hi << 32);
+                    for (int q = 0; q < NB / 2; ++q) {
+                        const int w = cg * (NB / 2) + q;
+                        const uint64_t lo = wl[lane * NB + 2 * q];
+                        const uint64_t hi = wl[lane * NB + 2 * q + 1];
+                        if (w < Cw)
+                            bits[(pix0 + lane) * Cw + w] = lo | (hi << 32);
+                    }
                 }
             }
         }
@@ -608,12 +622,14 @@ static int conv_f32_launch(const float *in, const float *filt, float *out, const
     if (!(C == 3 && kh == 3 && kw == 3 && stride == 1 && (int64_t)H * W * C < (1ll << 31) &&
           (int64_t)L2 * 27 < (1ll << 31)))
         return ESP_OK;
-    // channel groups of up to 128 (4 MFMA column blocks); one or three blocks only when L2 is
-    // that small, so that a group always starts on a word boundary
-    const int nb = L2 <= 32 ? 1 : (L2 <= 64 ? 2 : 4);
-    const int cgroups = (L2 + nb * 32 - 1) / (nb * 32);
+    // a wave takes 128 output channels (4 MFMA column blocks, whole output words), or, when
+    // that leaves most SIMDs without a wave (small batches), 32 channels = a 32-bit piece of a
+    // word; either way the groups cover every word completely (channels beyond L2 give 0 bits)
     const int strips = (W2 + 31) / 32;
     const int64_t rows_strips = (int64_t)B * H2 * strips;
+    const int64_t Cw = ceil_div(L2, 64);
+    const int nb = rows_strips * ceil_div(L2, 128) < 1024 ? 1 : 4;
+    const int64_t cgroups = nb == 1 ? 2 * Cw : ceil_div(L2, 128);
     const int64_t tasks = rows_strips * cgroups;
     if (tasks >= (1ll << 31))
         return ESP_OK;
@@ -627,15 +643,11 @@ static int conv_f32_launch(const float *in, const float *filt, float *out, const
     if (bits) {
         if (nb == 1)
             ESP_CONV1(1, true);
-        else if (nb == 2)
-            ESP_CONV1(2, true);
         else
             ESP_CONV1(4, true);
     } else {
         if (nb == 1)
             ESP_CONV1(1, false);
-        else if (nb == 2)
-            ESP_CONV1(2, false);
         else
             ESP_CONV1(4, false);
     }
