@@ -32,6 +32,7 @@ CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
 # One v_xor_b32 + one accumulating v_bcnt_u32_b32 per lane handle 32 binary MACs = 64 bop.
 VALU_PEAK_TBOPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ * 64 / 2 / 1e12      # 1258.3 Tbop/s
 HBM_PEAK_GBS = 8000.0
+BGEMM_8192_TRAFFIC_BYTES = int((2.0 * 37184 + 262144) * 1024)   # measured, see profiles/bgemm_8192_cube.txt
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 MFMA
 MFMA_FP4_PEAK_TOPS = 10100.0   # dense fp4/fp6 MFMA, TFLOP/s; one binary MAC = 2 flop = 2 bop
 
@@ -148,7 +149,12 @@ def main() -> int:
                    "pct_of_int_valu_peak": round(100.0 * tbops / VALU_PEAK_TBOPS, 2)},
         "roofline": {"bound": "alu", "kernel": "bgemm_tile_kernel", "achieved": round(tbops, 2),
                      "peak": round(VALU_PEAK_TBOPS, 1), "unit": "Tbop/s",
-                     "frac": round(tbops / VALU_PEAK_TBOPS, 4), "traffic": None,
+                     "frac": round(tbops / VALU_PEAK_TBOPS, 4),
+                     # HBM bytes per launch from the committed counter runs of this command
+                     # (profiles/bgemm_8192_cube.txt): 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
+                     "traffic": BGEMM_8192_TRAFFIC_BYTES if n == 8192 else None,
+                     "traffic_detail": "read 2.0 x 37184 KiB + written 262144 KiB per launch (rocprofv3 --pmc "
+                                       "FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy)" if n == 8192 else None,
                      "algorithmic_bop_per_launch": bop,
                      "algorithmic_bytes_per_launch": 2 * n * n // 8 + 4 * n * n},
         "paper_context": "Sec. 6.1 Table 1: 11 ms for this product on a GTX 960 (64-bit packing)",
