@@ -93,9 +93,9 @@ def test_bgemm_mfma(M, N, K):
     assert np.array_equal(got, oracle.dense_pm1(a, b))
 
 
-# the matrix-core kernel's three block shapes, each checked in full against the oracle with
-# ragged edges: 256 x 128 (small products), 256 x 256 (N > 128, at least 256 blocks) and
-# 512 x 128 (N <= 128, M >= 131072); int32 and thresholded outputs
+# the matrix-core kernel checked in full against the oracle on large products with ragged edges
+# (thousands of 256 x 128 blocks, many tile rows per XCD group, a very tall and narrow product);
+# int32 and thresholded outputs
 @pytest.mark.parametrize("M,N,K", [(4100, 4100, 200), (131072 + 70, 100, 192), (2000, 300, 1100)])
 def test_bgemm_mfma_block_shapes(M, N, K):
     rng = np.random.default_rng(M + 3 * N + 7 * K)
