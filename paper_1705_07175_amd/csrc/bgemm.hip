@@ -375,6 +375,116 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
     return launch_tile2<32, 64, 2, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
 }
 
+// ---------------------------------------------------------------------------------
+// Few-rows kernel with the threshold epilogue (the convolutions and dense layers of a network
+// evaluated one image at a time, Sec. 6.2 / 6.3: M is a few hundred rows at most).  The tiled
+// kernel would give such a product 16-32 blocks whose lanes each walk all of K; here the work
+// is spread the other way round:
+//  * a wave owns 64 rows of A, lane = row, and kNB = 8 rows of B whose 16-byte chunks are the
+//    same for every lane (uniform addresses: they travel through the scalar data path and
+//    enter the XOR as scalar operands);
+//  * the waves of a block split K: wave w takes chunks w, w + W, ..., and the per-lane
+//    mismatch counts of the W waves meet in LDS;
+//  * 8 columns = one byte of the packed output row; the grid covers every byte of every word
+//    (columns beyond N give zero bits);
+//  * a fused 2x2 max-pool ORs the bytes of lanes l, l^1, l^W2, l^(W2+1) (64 rows are whole
+//    pairs of image rows when W2 <= 32).
+// ---------------------------------------------------------------------------------
+constexpr int kFewNB = 8;
+
+template <class ASrc>
+__global__ __launch_bounds__(1024)
+void bfew_bits_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const int32_t *__restrict__ thr,
+                      const uint64_t *__restrict__ flip, uint8_t *__restrict__ out, int M, int N,
+                      int K_true, int row_dw, int pool_log2w)
+{
+    constexpr int NB = kFewNB;
+    __shared__ int red[NB][kWave];
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int W = blockDim.x / kWave;
+    const int m0 = blockIdx.x * kWave;
+    const int piece = blockIdx.y;            // byte of the packed output row
+    const int n0 = piece * NB;
+    for (int i = threadIdx.x; i < NB * kWave; i += blockDim.x)
+        (&red[0][0])[i] = 0;
+
+    const typename ASrc::Row arow = asrc.row_nb(m0 + lane);
+    const uint32_t *brow[NB];                // uniform; rows beyond N read the last row
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        brow[j] = B + (int64_t)min(n0 + j, N - 1) * row_dw;
+    int acc[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        acc[j] = 0;
+    const int nch = row_dw / 4;
+    for (int c = wave; c < nch; c += W) {
+        const int kd = c * 4;
+        const uint4 a = asrc.fetch_nb(arow, asrc.step(kd), kd);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const uint4 b = *reinterpret_cast<const uint4 *>(brow[j] + kd);
+            acc[j] += __popc(a.x ^ b.x) + __popc(a.y ^ b.y) + __popc(a.z ^ b.z) + __popc(a.w ^ b.w);
+        }
+    }
+    __syncthreads();                         // red is zero
+    if (W > 1) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            atomicAdd(&red[j][lane], acc[j]);
+        __syncthreads();
+    }
+    if (wave != 0)
+        return;
+    uint32_t byte = 0;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int n = n0 + j;
+        const int a = W > 1 ? red[j][lane] : acc[j];
+        // dot = K - 2a >= thr  <=>  a <= floor((K - thr) / 2); columns beyond N: bit 0
+        const int t = min(max(thr[min(n, N - 1)], -K_true), K_true + 1);
+        byte |= (n < N && a <= ((K_true - t) >> 1)) ? 1u << j : 0u;
+    }
+    byte ^= (uint32_t)(flip[piece / 8] >> (8 * (piece % 8))) & 0xffu;
+    const int pieces = gridDim.y;            // bytes per packed output row
+    const int r = m0 + lane;
+    if (pool_log2w == 0) {
+        if (r < M)
+            out[(int64_t)r * pieces + piece] = (uint8_t)byte;
+        return;
+    }
+    const int W2 = 1 << pool_log2w;
+    byte |= (uint32_t)__shfl_xor((int)byte, 1, kWave);
+    byte |= (uint32_t)__shfl_xor((int)byte, W2, kWave);
+    if ((lane & 1) == 0 && (lane & W2) == 0 && r < M) {
+        const int line = r >> pool_log2w, n = r & (W2 - 1);
+        const int64_t prow = (int64_t)(line >> 1) * (W2 >> 1) + (n >> 1);
+        out[prow * pieces + piece] = (uint8_t)byte;
+    }
+}
+
+// Does the few-rows kernel apply?  Rows that the tiled kernel's smallest tiles would spread
+// over less than one block per CU, 16-byte chunks, and (pooled) whole row pairs in 64 rows.
+static bool few_rows_ok(int64_t M, int64_t N, int64_t row_dw, int pool_log2w)
+{
+    return ceil_div(M, 32) * ceil_div(N, 64) < 256 && row_dw % 4 == 0 && row_dw / 4 < (1 << 20) &&
+           ceil_div(M, 64) < 65536 && ceil_div(N, 64) * 8 < 65536 && (pool_log2w == 0 || pool_log2w <= 5);
+}
+
+template <class ASrc>
+static int launch_few(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
+                      int64_t K_true, int64_t row_dw, hipStream_t stream)
+{
+    const int64_t nch = row_dw / 4;
+    const int waves = (int)(nch < 16 ? nch : 16);        // the waves of a block split K
+    const dim3 grid((unsigned)ceil_div(M, 64), (unsigned)(ceil_div(N, 64) * 8)), block((unsigned)(waves * kWave));
+    hipLaunchKernelGGL((bfew_bits_kernel<ASrc>), grid, block, 0, stream, asrc, b, o.thr, o.flip,
+                       reinterpret_cast<uint8_t *>(o.bits), (int)M, (int)N, (int)K_true, (int)row_dw,
+                       o.pool_log2w);
+    return launch_status();
+}
+
 static int tile_matrix(const uint64_t *A, const uint64_t *B, const TileOut &o, int64_t M, int64_t N,
                        int64_t K_true, int64_t row_words, hipStream_t stream)
 {
@@ -382,6 +492,8 @@ static int tile_matrix(const uint64_t *A, const uint64_t *B, const TileOut &o, i
     const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
     const int row_dw = (int)(row_words * 2);
+    if (vec16 && o.bits && few_rows_ok(M, N, row_dw, 0))
+        return launch_few(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw, stream);
     if (vec16)
         return launch_tile<MatrixA<true>, true>(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true,
                                                 row_dw, stream);
@@ -746,6 +858,9 @@ int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_o
     o.thr = thr;
     o.flip = flip;
     o.pool_log2w = pool_log2w;
+    if (bits_out && few_rows_ok(M, L2, row_dw, pool_log2w))
+        return launch_few(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2, (int64_t)kh * kw * C, row_dw,
+                          stream);
     return launch_tile<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2,
                                     (int64_t)kh * kw * C, row_dw, stream);
 }
