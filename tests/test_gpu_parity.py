@@ -298,6 +298,23 @@ def test_bgemm_bn_sign_pack(M, N, K, engine):
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
+# products with few rows take the kernel that splits K over the waves of a block (lane = row,
+# 8 columns = one output byte per block): K from one 16-byte chunk to more chunks than waves,
+# M around the 64-row groups, N around the byte and word boundaries
+@pytest.mark.parametrize("M,N,K", [(9, 8, 128), (63, 9, 256), (64, 64, 4608), (65, 71, 2304), (200, 130, 1152),
+                                   (256, 256, 2304), (1000, 100, 384), (33, 500, 8192 + 128), (12, 1024, 8192)])
+def test_bgemm_bn_sign_pack_few_rows(M, N, K):
+    rng = np.random.default_rng(M * 3 + N * 5 + K)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    got = esp.bgemm_bn_sign_pack(_packed_dev(a), _packed_dev(b), K, torch.from_numpy(thr).to(DEV),
+                                 esp.to_packed_tensor(flip, DEV))
+    want = oracle.pack_bits(oracle.bn_sign(oracle.dense_pm1(a, b), bnp, synth.BN_EPS))
+    assert np.array_equal(esp.packed_to_numpy(got), want)
+
+
 @pytest.mark.parametrize("engine", [0, 1])
 def test_bgemm_bn_sign_pack_large_tiles(engine):
     M, N, K = 2900, 2950, 640
@@ -354,6 +371,9 @@ POOL_CONV_CASES = [
     (2, 16, 8, 128, 64, 3, 3, 2, 1),       # stride 2: H2 = 8, W2 = 4
     (1, 6, 64, 128, 64, 3, 3, 1, 1),       # W2 = 64: 128-row tiles although the product is small
     (7, 2, 2, 256, 192, 1, 1, 1, 0),       # 1x1 filter, one pooled pixel per image
+    (2, 8, 32, 128, 72, 3, 3, 1, 1),       # few rows, W2 = 32: pool partners in the other half-wave
+    (1, 10, 4, 384, 200, 3, 3, 1, 1),      # few rows, H2 = 10: last 64-row group half empty
+    (1, 4, 64, 128, 16, 3, 3, 1, 1),       # few rows but W2 = 64: tiled kernel
 ]
 
 
