@@ -24,6 +24,8 @@
 // 15 % slower than FN = 2 with two waves per SIMD, so only the latter is instantiated; with
 // the operand ANDs, the popcounts and the epilogue all removed the time did not change, the
 // loads of a stage (global -> registers -> LDS) and the barrier are what the MFMAs wait for.
+#include <type_traits>
+
 #include "esp_internal.h"
 #include "tile_sources.h"
 
@@ -162,6 +164,27 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         }
     };
 
+    // operand lane mapping of the 32x32x64 MFMA: row/column = lane % 32, k half = lane / 32
+    const int lr = lane % 32, half = lane / 32;
+
+    // thresholds and flip words of the lane's columns, fetched now so that the epilogue does not
+    // start with a memory round trip (clamped: K + 1 can never be reached, tail bits stay 0)
+    constexpr int NW = FN / 2;
+    int lim[FN];
+    uint64_t fl[NW];
+    if (BITS) {
+#pragma unroll
+        for (int g = 0; g < FN; ++g) {
+            const int col = n0 + wn + g * 32 + lr;
+            lim[g] = col < N ? min(max(o.thr[col], -K_true), K_true + 1) : K_true + 1;
+        }
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int wi = ((n0 + wn) >> 6) + w;
+            fl[w] = wi < o.Nw ? o.flip[wi] : 0ull;
+        }
+    }
+
     v16f acc[4][FN];
 #pragma unroll
     for (int f = 0; f < 4; ++f)
@@ -171,8 +194,6 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             for (int r = 0; r < 16; ++r)
                 acc[f][g][r] = 0.0f;
 
-    // operand lane mapping of the 32x32x64 MFMA: row/column = lane % 32, k half = lane / 32
-    const int lr = lane % 32, half = lane / 32;
     const int stages = (row_dw + STAGE_DW - 1) / STAGE_DW;
     prefetch(0);
     commit(0);
@@ -183,6 +204,8 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             prefetch(s + 1);                 // global loads in flight during this stage's MFMAs
 #pragma unroll
         for (int step = 0; step < KG / 2; ++step) {
+            if ((s * KG + 2 * step) * 4 >= row_dw)
+                continue;                    // both k-groups of this step lie beyond the row
             const int kg = 2 * step + half;
             uint4 xa[4], xb[FN];
 #pragma unroll
@@ -218,69 +241,82 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         kb[g] = K_true - 2 * pb_s[wn + g * 32 + lr];
 
     if (BITS) {
-        // a 64-column word per row and pair of column blocks: the comparison masks of the two
-        // blocks are its halves (lanes 0-31: row R, lanes 32-63: row R + 4)
-        constexpr int NW = FN / 2;
-        int lim[FN];
+        // dot >= thr  <=>  4 c + (K - 2 pb - thr) >= 2 pa  <=>  c >= pa / 2 - (K - 2 pb - thr) / 4.
+        // For K < 2^20 the right-hand side is exact in fp32 (multiples of 1/4 below 2^22) and c is
+        // the fp32 accumulator itself, so the decision is one add and one compare; longer K takes
+        // the integer form.  The 64-lane mask of a comparison holds, for one column block, the 32
+        // bits of row R (lanes 0-31) and of row R + 4 (lanes 32-63); the flip bits are XORed into
+        // the masks as scalars.  Lanes 0 and 32 then drop the two rows' 64-column words (low half
+        // from the even block, high half from the odd one) into the block's word table in LDS
+        // (the A slabs are free by now), from where each lane picks up the words of its rows.
+        constexpr int WPT = BN / 64;
+        uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0][0]);
+        const bool fp_exact = K_true < (1 << 20);
+        int ct[FN];
+        float ctf[FN];
 #pragma unroll
         for (int g = 0; g < FN; ++g) {
-            const int col = n0 + wn + g * 32 + lr;
-            lim[g] = col < N ? o.thr[col] : 0x7fffffff;   // never reached beyond N: tail bits 0
+            ct[g] = kb[g] - lim[g];
+            ctf[g] = -0.25f * (float)ct[g];
         }
-        uint64_t mine[2][NW];   // lane L keeps the words of wave-tile rows L and 64 + L
+        uint64_t flx[FN];   // flip bits of column block g, in both halves of a mask
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int w = 0; w < NW; ++w) {
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)fl[w]);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(fl[w] >> 32));
+            flx[2 * w] = ((uint64_t)lo << 32) | lo;
+            flx[2 * w + 1] = ((uint64_t)hi << 32) | hi;
+        }
+        auto rows_to_table = [&](auto exact) {
 #pragma unroll
-            for (int q = 0; q < NW; ++q)
-                mine[h][q] = 0;
+            for (int f = 0; f < 4; ++f)
 #pragma unroll
-        for (int f = 0; f < 4; ++f)
+                for (int q = 0; q < 4; ++q) {
+                    const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[wm + f * 32 + 8 * q + 4 * half]);
+                    const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
+                    uint64_t mask[4][FN];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[wm + f * 32 + 8 * q + 4 * half]);
-                const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
+                    for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int r = 4 * q + t;
-                    const int R = f * 32 + 8 * q + t;                                     // compile-time
+                        for (int g = 0; g < FN; ++g) {
+                            bool ge;
+                            if (decltype(exact)::value)
+                                ge = acc[f][g][4 * q + t] >= 0.5f * (float)pav[t] + ctf[g];
+                            else
+                                ge = 4 * (int)acc[f][g][4 * q + t] + ct[g] >= 2 * pav[t];
+                            mask[t][g] = __ballot(ge) ^ flx[g];
+                        }
+                    if (lr == 0) {
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) {
-                        const uint64_t m0b =
-                            __ballot(4 * (int)acc[f][2 * w][r] + kb[2 * w] - 2 * pav[t] >= lim[2 * w]);
-                        const uint64_t m1b =
-                            __ballot(4 * (int)acc[f][2 * w + 1][r] + kb[2 * w + 1] - 2 * pav[t] >= lim[2 * w + 1]);
-                        const uint64_t w_lo = (m0b & 0xffffffffull) | (m1b << 32);          // row R
-                        const uint64_t w_hi = (m0b >> 32) | (m1b & 0xffffffff00000000ull);   // row R + 4
-                        if (lane == R % 64)
-                            mine[R / 64][w] = w_lo;
-                        if (lane == (R + 4) % 64)
-                            mine[(R + 4) / 64][w] = w_hi;
+                        for (int t = 0; t < 4; ++t) {
+                            const int row = wm + f * 32 + 8 * q + 4 * half + t;
+#pragma unroll
+                            for (int w = 0; w < NW; ++w) {
+                                const uint32_t lo = (uint32_t)(mask[t][2 * w] >> (32 * half));
+                                const uint32_t hi = (uint32_t)(mask[t][2 * w + 1] >> (32 * half));
+                                wt[row * WPT + (wn >> 6) + w] = ((uint64_t)hi << 32) | lo;
+                            }
+                        }
                     }
                 }
-            }
+        };
+        if (fp_exact)
+            rows_to_table(std::true_type{});
+        else
+            rows_to_table(std::false_type{});
         const int w0 = (n0 + wn) >> 6;
-        uint64_t fl[NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w)
-            fl[w] = w0 + w < o.Nw ? o.flip[w0 + w] : 0ull;
         if (o.pool_log2w == 0) {
+            __builtin_amdgcn_wave_barrier();     // a wave reads back only what it wrote itself
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int row = m0 + wm + h * 64 + lane;
+                const int rl = wm + h * 64 + lane;
 #pragma unroll
                 for (int w = 0; w < NW; ++w)
-                    if (row < M && w0 + w < o.Nw)
-                        o.bits[(int64_t)row * o.Nw + w0 + w] = mine[h][w] ^ fl[w];
+                    if (m0 + rl < M && w0 + w < o.Nw)
+                        o.bits[(int64_t)(m0 + rl) * o.Nw + w0 + w] = wt[rl * WPT + (wn >> 6) + w];
             }
         } else {
-            // OR max-pool: the tile's words meet in LDS (the A slabs are free by now)
-            constexpr int WPT = BN / 64;
-            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0][0]);
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int w = 0; w < NW; ++w)
-                    wt[(wm + h * 64 + lane) * WPT + (wn >> 6) + w] = mine[h][w] ^ fl[w];
+            // OR max-pool over the whole block tile
             __syncthreads();
             pool_tile_store<BM, WPT, NT>(wt, o.bits, m0, n0, M, o.Nw, o.pool_log2w, tid);
         }

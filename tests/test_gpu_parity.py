@@ -283,7 +283,8 @@ SMALL_M_BITS = [(1, 4096, 4096), (2, 100, 70), (3, 1024, 1024), (4, 130, 192), (
 
 @pytest.mark.parametrize("engine", [0, 1])
 @pytest.mark.parametrize("M,N,K", SMALL_M_BITS + [(1, 64, 64), (9, 10, 4096), (64, 4096, 1024), (130, 70, 200), (257, 513, 1152),
-                                   (1000, 128, 1152), (5, 1024, 8192), (1024, 1024, 1024)])
+                                   (1000, 128, 1152), (5, 1024, 8192), (1024, 1024, 1024),
+                                   (64, 70, (1 << 20) + 64)])    # K >= 2^20: integer threshold compare on the matrix cores
 def test_bgemm_bn_sign_pack(M, N, K, engine):
     rng = np.random.default_rng(M * 31 + N * 17 + K)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
