@@ -125,6 +125,27 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bconv_bn_sign_pack_pool2(p, p, p, p, p, 0, 8, 8, 128, 8, 3, 3, 1, 1, 0, None) == 0
 
 
+def test_empty_batches_are_no_ops_without_a_gpu():
+    # a zero batch / zero rows returns ESP_OK before anything is launched (no GPU here)
+    lib = esp.lib()
+    buf = (ctypes.c_uint64 * 64)()
+    p = ctypes.addressof(buf)
+    assert lib.esp_unroll(p, p, 0, 4, 4, 64, 3, 3, 1, 1, None) == 0
+    assert lib.esp_bconv(p, p, p, 0, 4, 4, 64, 8, 3, 3, 1, 1, None, 0, None) == 0
+    assert lib.esp_bconv_mfma(p, p, p, 0, 4, 4, 64, 8, 3, 3, 1, 1, None, 0, None) == 0
+    assert lib.esp_bconv_bn_sign_pack(p, p, p, p, p, 0, 4, 4, 64, 8, 3, 3, 1, 1, None, 0, 0, None) == 0
+    assert lib.esp_bgemm_bn_sign_pack(p, p, p, p, p, 0, 4, 64, 2, None) == 0
+    assert lib.esp_bgemm_mfma(p, p, p, 0, 4, 64, None) == 0
+    assert lib.esp_bmaxpool(p, p, 0, 4, 4, 64, 2, 2, None) == 0
+    assert lib.esp_bn_sign_pack(p, p, p, p, 0, 64, None) == 0
+    assert lib.esp_bn_sign_pack_f32(p, p, p, p, 0, 64, None) == 0
+    assert lib.esp_dense_f32(p, p, p, 0, 4, 4, None) == 0
+    assert lib.esp_conv_f32(p, p, p, 0, 4, 4, 3, 8, 3, 3, 1, 1, None) == 0
+    assert lib.esp_conv_f32_bn_sign_pack(p, p, p, p, p, None, 0, 4, 4, 3, 8, 3, 3, 1, 1, None) == 0
+    assert lib.esp_bitplane_pack_u8(p, p, 0, 1, 64, None) == 0
+    assert lib.esp_bitplane_combine(p, p, p, 0, 1, 4, None) == 0
+
+
 def _check_fold(gamma, beta, mean, var, eps, lo, hi):
     thr, flip = esp.bn_fold(gamma, beta, mean, var, eps)
     C = len(gamma)
