@@ -64,8 +64,11 @@ enum esp_engine {
     ESP_ENGINE_XOR_POPCOUNT = 0, /* vector ALU: v_xor + v_bcnt (the paper's XNOR/bit-count) */
     ESP_ENGINE_MFMA = 1,         /* matrix cores: bits expanded to 4-bit float operands      */
     ESP_ENGINE_AUTO = 2          /* matrix cores when the product fills the chip with their  */
-                                 /* 256 x 128 tiles, the vector ALU's small tiles otherwise  */
+                                 /* 256 x 128 tiles, the vector ALU otherwise                */
 };
+/* On the vector ALU a product is tiled (128 x 128 down to 32 x 64 outputs per block) or, when */
+/* it has few rows (a network evaluated on one or a few images), split over K instead; with    */
+/* ESP_ENGINE_MFMA every product goes to the matrix cores whatever its size.                   */
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char *esp_strerror(int status);
