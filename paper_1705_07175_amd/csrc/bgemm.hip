@@ -531,7 +531,7 @@ template <int MS, bool VEC16, bool A_LDS>
 __global__ __launch_bounds__(256)
 void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B,
                   int32_t *__restrict__ C, int M, int N, int K_true, int row_words, int lpr,
-                  int groups_per_wave)
+                  int groups_per_wave, int64_t c_stride_m, int64_t c_stride_row)
 {
     using CK = Chunk<VEC16>;
     using chunk_t = typename CK::type;
@@ -596,7 +596,7 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
 #pragma unroll
             for (int m = 0; m < MS; ++m)
                 if (m < M)
-                    C[(int64_t)m * N + row] = K_true - 2 * acc[m];
+                    C[m * c_stride_m + row * c_stride_row] = K_true - 2 * acc[m];
         }
     }
 }
@@ -604,9 +604,12 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
 constexpr size_t kGemvLdsBytes = 64 * 1024;
 constexpr int kGemvMaxM = 8;   // rows of A the small-M kernels take
 
+// C[m * c_stride_m + n * c_stride_row] = dot(A row m, B row n): strides (N, 1) for the plain
+// product, (1, M') when the caller has swapped the operands of a product with few columns.
 template <int MS, bool VEC16>
 static int launch_gemv2(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
-                        int64_t K_true, int64_t row_words, hipStream_t stream)
+                        int64_t K_true, int64_t row_words, int64_t c_stride_m, int64_t c_stride_row,
+                        hipStream_t stream)
 {
     const int nch = (int)(row_words / (VEC16 ? 2 : 1));
     int lpr = 1;
@@ -623,20 +626,21 @@ static int launch_gemv2(const uint64_t *A, const uint64_t *B, int32_t *C, int64_
     const size_t lds = (size_t)MS * row_words * 8;
     if (lds <= kGemvLdsBytes)
         hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, true>), dim3(grid), dim3(256), lds, stream, A, B, C,
-                           (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw);
+                           (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw, c_stride_m, c_stride_row);
     else
         hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, false>), dim3(grid), dim3(256), 0, stream, A, B, C,
-                           (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw);
+                           (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw, c_stride_m, c_stride_row);
     return launch_status();
 }
 
 template <int MS>
 static int launch_gemv(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int64_t N,
-                       int64_t K_true, int64_t row_words, hipStream_t stream)
+                       int64_t K_true, int64_t row_words, hipStream_t stream, bool swapped = false)
 {
     const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
-    return vec16 ? launch_gemv2<MS, true>(A, B, C, M, N, K_true, row_words, stream)
-                 : launch_gemv2<MS, false>(A, B, C, M, N, K_true, row_words, stream);
+    const int64_t sm = swapped ? 1 : N, sr = swapped ? M : 1;
+    return vec16 ? launch_gemv2<MS, true>(A, B, C, M, N, K_true, row_words, sm, sr, stream)
+                 : launch_gemv2<MS, false>(A, B, C, M, N, K_true, row_words, sm, sr, stream);
 }
 
 // ---------------------------------------------------------------------------------
@@ -799,6 +803,13 @@ int bgemm_launch(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, in
         return launch_gemv<4>(A, B, C, M, N, K_true, row_words, stream);
     if (M <= 8)
         return launch_gemv<8>(A, B, C, M, N, K_true, row_words, stream);
+    // few columns (the 10 scores of the last layer): the same kernel with the operands swapped,
+    // the few weight rows in LDS, the many activation rows streamed, C written transposed
+    if (N <= 16 && (size_t)16 * row_words * 8 <= kGemvLdsBytes) {
+        if (N <= 8)
+            return launch_gemv<8>(B, A, C, N, M, K_true, row_words, stream, true);
+        return launch_gemv<16>(B, A, C, N, M, K_true, row_words, stream, true);
+    }
     TileOut o;
     o.C = C;
     return tile_matrix(A, B, o, M, N, K_true, row_words, stream);

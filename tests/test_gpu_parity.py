@@ -74,6 +74,8 @@ BGEMM_SHAPES = [
     (5, 33, 100), (7, 2048, 1152), (8, 10, 4096), (1, 10, 1024),             # small-M kernel
     (9, 10, 4096), (64, 1024, 1024), (130, 70, 200), (257, 513, 1152),       # 64x64 tiles
     (100, 1000, 64), (65, 129, 4608), (1024, 10, 1024), (300, 301, 8256),
+    (1024, 10, 4096), (100, 16, 200), (9, 1, 64), (300, 8, 8256), (64, 9, 8192), (2000, 3, 70),   # few columns
+    (33, 17, 128),
 ]
 
 
