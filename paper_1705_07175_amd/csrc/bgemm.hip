@@ -1,7 +1,7 @@
 // Binary matrix product on packed words (Sec. 4.2, Eq. 2 of arXiv 1705.07175):
 //   C[m][n] = K - 2 * sum_w popcount(A[m][w] XOR B[n][w]).
 //
-// Two kernels:
+// Four kernels:
 //  * bgemm_tile_kernel  -- compute-bound case.  A block stages BM x 1024-bit and
 //    BN x 1024-bit slabs of the packed rows in LDS as 16-byte k-groups, every lane
 //    keeps a TM x TN tile of int32 mismatch counters in registers and runs a pure
@@ -15,7 +15,11 @@
 //    the int32 dot products or, with the folded batch-norm threshold, the packed
 //    sign bits of the next layer (the bit-packing sign activation of Sec. 6.3).
 //  * bgemv_kernel       -- small M (matrix-vector, Sec. 6.2 "Optimized kernels"):
-//    bandwidth-bound streaming of B with the few A rows held in LDS.
+//    bandwidth-bound streaming of B with the few A rows held in LDS; also used with
+//    the operands swapped for products with few columns (the 10 scores of a network).
+//  * bgemv_bits_kernel  -- the same with the threshold + sign + pack epilogue.
+//  * bfew_bits_kernel   -- products of a few hundred rows (a network's convolutions at
+//    batch 1): lane = row, K split over the waves of a block, threshold epilogue.
 #include "esp_internal.h"
 #include "tile_sources.h"
 
