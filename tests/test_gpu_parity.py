@@ -178,6 +178,37 @@ def test_bgemm_closed_forms_on_gpu():
     assert np.all(np.diag(c) == -K)
 
 
+@pytest.mark.parametrize("M", [1, 9])
+def test_bgemm_longest_rows_closed_forms(M):
+    # the longest legal rows (K = 2^30 - 64: 128 MiB per packed row); the oracle's unpacked
+    # operands would not fit, so the expected values are closed forms: equal rows give +K,
+    # complementary rows -K, one differing word K - 128 (the int32 contract at its edge)
+    K = (1 << 30) - 64
+    Kw = K // 64
+    a = torch.full((M, Kw), -1, dtype=esp.PACKED, device=DEV)          # all +1
+    b = torch.full((3, Kw), -1, dtype=esp.PACKED, device=DEV)
+    b[1].zero_()                                                       # all -1
+    b[2, Kw // 2] = 0                                                  # 64 values differ
+    c = esp.bgemm(a, b, K).cpu().numpy()
+    assert np.array_equal(c, np.tile(np.array([K, -K, K - 128], dtype=np.int32), (M, 1)))
+    lib_status = esp.lib().esp_bgemm(a.data_ptr(), b.data_ptr(), a.data_ptr(), M, 3, 1 << 30, None)
+    assert lib_status == -3                                            # K = 2^30 is refused
+
+
+def test_bgemm_mfma_longest_rows_closed_forms():
+    K = (1 << 24) - 64                                                 # fp32-exact accumulation limit
+    Kw = K // 64
+    a = torch.full((9, Kw), -1, dtype=esp.PACKED, device=DEV)
+    a[3].zero_()
+    b = torch.full((3, Kw), -1, dtype=esp.PACKED, device=DEV)
+    b[1].zero_()
+    b[2, 7] = 0
+    want = np.tile(np.array([K, -K, K - 128], dtype=np.int32), (9, 1))
+    want[3] = [-K, K, -(K - 128)]
+    assert np.array_equal(esp.bgemm_mfma(a, b, K).cpu().numpy(), want)
+    assert np.array_equal(esp.bgemm(a, b, K).cpu().numpy(), want)
+
+
 def test_bgemm_unaligned_views():
     # rows of odd word count and a base pointer that is only 8-byte aligned
     M, N, K = 20, 30, 192
