@@ -276,10 +276,9 @@ int esp_conv_f32(const float *in, const float *filt, float *out,
 /* shapes without a fused kernel `pre` is required as scratch                 */
 /* (ESP_EWORKSPACE if NULL).                                                  */
 /*                                                                            */
-/* dense_f32_bn_sign_pack: esp_dense_f32 followed by esp_bn_sign_pack_f32;    */
-/* `bits` uint64 [M][ceil(N/64)] is always written, `pre` (float [M][N]) only */
-/* if not NULL.  Up to M = 4 (one image at a time, Sec. 6.2) this is a single */
-/* kernel; for larger M `pre` is required as scratch (ESP_EWORKSPACE if NULL).*/
+/* dense_f32_bn_sign_pack: esp_dense_f32 followed by esp_bn_sign_pack_f32 in  */
+/* one kernel; `bits` uint64 [M][ceil(N/64)] is always written, `pre` (float  */
+/* [M][N], the pre-activations) only if not NULL.                             */
 /* ------------------------------------------------------------------------- */
 int esp_bn_fold_f32(const float *gamma, const float *beta, const float *mean, const float *var,
                     float eps, int C, float *thr, float *sgn);

@@ -360,7 +360,7 @@ def dense_f32(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None)
 def dense_f32_bn_sign_pack(x: torch.Tensor, w: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
                            out: torch.Tensor | None = None, pre: torch.Tensor | None = None) -> torch.Tensor:
     """``esp_dense_f32_bn_sign_pack``: float dense layer + folded batch-norm + sign -> packed [M][Nw].
-    ``pre`` (float [M][N]) receives the pre-activations if given; it is required for M > 4."""
+    ``pre`` (float [M][N]) receives the pre-activations if given."""
     px, pw = _dev(x, torch.float32, "x"), _dev(w, torch.float32, "w")
     M, K = x.shape
     N, K2 = w.shape

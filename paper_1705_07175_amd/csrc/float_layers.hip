@@ -19,10 +19,15 @@ namespace esp {
 // Result layout of the MFMA: lane -> column lane % 32, register r -> row 8 (r/4) + 4 (lane/32) + r%4.
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int BN, bool VEC4>
+// With FUSE the folded batch-norm threshold + sign is applied in the epilogue (bit n of row m =
+// (sgn[n] * y >= thr[n])): the 64-lane mask of a comparison holds 32 column bits of two rows,
+// lanes 0 and 32 drop them into an LDS table and 64 threads store one packed word (BN = 64)
+// or one 32-bit half of a word (BN = 32) per row; Y is then written only if not null.
+template <int BN, bool VEC4, bool FUSE>
 __global__ __launch_bounds__(256)
 void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
-                           float *__restrict__ Y, int M, int N, int K)
+                           float *__restrict__ Y, const float *__restrict__ thr,
+                           const float *__restrict__ sgn, uint64_t *__restrict__ bits, int M, int N, int K)
 {
     constexpr int BM = 64, BK = 32;
     constexpr int XQ = BM * BK / 4 / 256;   // float4 units per thread and slab: 2
@@ -84,6 +89,11 @@ void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict_
     const int wm = (wave % 2) * 32;          // wave's row offset
     const int wn = WN == 2 ? (wave / 2) * 32 : 0;
     const int kpart = WN == 2 ? 0 : wave / 2;   // BN = 32: which of the alternate k-steps
+    float th = 0.0f, sg = 1.0f;              // FUSE: threshold and sign of the lane's column, fetched early
+    if (FUSE && n0 + wn + lr < N) {
+        th = thr[n0 + wn + lr];
+        sg = sgn[n0 + wn + lr];
+    }
     v16f acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -101,27 +111,50 @@ void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict_
         }
         __syncthreads();
     }
+    bool owner = true;                       // this wave holds finished sums
     if (WN == 1) {
         // the wave pairs 0,1 and 2,3 hold partial sums of the same 64 x 32 tile
         float *red = &Xs[0][0];              // 32 x 68 floats >= 2 waves x 16 x 64
-        if (wave >= 2) {
+        owner = wave < 2;
+        if (!owner) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 red[((wave - 2) * 16 + r) * kWave + lane] = acc[r];
         }
         __syncthreads();
-        if (wave >= 2)
-            return;
+        if (owner) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            acc[r] += red[(wave * 16 + r) * kWave + lane];
+            for (int r = 0; r < 16; ++r)
+                acc[r] += red[(wave * 16 + r) * kWave + lane];
+        }
     }
     const int n = n0 + wn + lr;
+    if (owner && (!FUSE || Y)) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm + 8 * (r / 4) + 4 * half + r % 4;
-        if (m < M && n < N)
-            Y[(int64_t)m * N + n] = acc[r];
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm + 8 * (r / 4) + 4 * half + r % 4;
+            if (m < M && n < N)
+                Y[(int64_t)m * N + n] = acc[r];
+        }
+    }
+    if (FUSE) {
+        __shared__ uint32_t wt[BM][WN];
+        if (owner) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint64_t mask = __ballot(n < N && sg * acc[r] >= th);
+                const uint32_t v = (uint32_t)(mask >> (32 * half));
+                if (lr == 0)
+                    wt[wm + 8 * (r / 4) + 4 * half + r % 4][wn / 32] = v;
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < M) {
+            if (WN == 2)   // one word per row; grid.x = words per row
+                bits[(int64_t)(m0 + tid) * gridDim.x + blockIdx.x] = wt[tid][0] | ((uint64_t)wt[tid][WN - 1] << 32);
+            else           // one 32-bit half per row; grid.x = halves per row
+                reinterpret_cast<uint32_t *>(bits)[(int64_t)(m0 + tid) * gridDim.x + blockIdx.x] = wt[tid][0];
+        }
     }
 }
 
@@ -511,6 +544,43 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
 
 } // namespace esp
 
+namespace esp {
+
+// Tiled float dense layer; with bits != null the fused threshold epilogue (Y then optional).
+static int dense_mfma_launch(const float *X, const float *W, float *Y, const float *thr, const float *sgn,
+                             uint64_t *bits, int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    const int64_t gy = ceil_div(M, 64);
+    if (gy > 65535)
+        return ESP_ESHAPE;
+    const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
+    const bool narrow = gy * ceil_div(N, 64) < 256;   // few blocks: halve the tile width
+    // the grid covers every word (or 32-bit half) of the packed rows, also columns beyond N
+    const int64_t Nw = ceil_div(N, 64);
+    const dim3 grid((unsigned)(narrow ? 2 * Nw : Nw), (unsigned)gy);
+#define ESP_DENSE(BN, V)                                                                                   \
+    do {                                                                                                   \
+        if (bits)                                                                                          \
+            hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
+                               bits, (int)M, (int)N, (int)K);                                              \
+        else                                                                                               \
+            hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
+                               bits, (int)M, (int)N, (int)K);                                              \
+    } while (0)
+    if (narrow && vec4)
+        ESP_DENSE(32, true);
+    else if (narrow)
+        ESP_DENSE(32, false);
+    else if (vec4)
+        ESP_DENSE(64, true);
+    else
+        ESP_DENSE(64, false);
+#undef ESP_DENSE
+    return launch_status();
+}
+
+} // namespace esp
+
 extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
                              int64_t M, int64_t N, int64_t K, esp_stream stream)
 {
@@ -534,24 +604,7 @@ extern "C" int esp_dense_f32(const float *X, const float *W, float *Y,
             hipLaunchKernelGGL((dense_f32_gemv_kernel<4>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K);
         return launch_status();
     }
-    const int64_t gy = ceil_div(M, 64);
-    if (gy > 65535)
-        return ESP_ESHAPE;
-    const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
-    const bool narrow = gy * ceil_div(N, 64) < 256;   // few blocks: halve the tile width
-    const dim3 grid((unsigned)ceil_div(N, narrow ? 32 : 64), (unsigned)gy);
-#define ESP_DENSE(BN, V) \
-    hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K)
-    if (narrow && vec4)
-        ESP_DENSE(32, true);
-    else if (narrow)
-        ESP_DENSE(32, false);
-    else if (vec4)
-        ESP_DENSE(64, true);
-    else
-        ESP_DENSE(64, false);
-#undef ESP_DENSE
-    return launch_status();
+    return dense_mfma_launch(X, W, Y, nullptr, nullptr, nullptr, M, N, K, s);
 }
 
 extern "C" int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const float *thr, const float *sgn,
@@ -570,17 +623,8 @@ extern "C" int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const 
     if (!aligned(X, 4) || !aligned(W, 4) || !aligned(thr, 4) || !aligned(sgn, 4) || !aligned(bits, 8) ||
         (pre && !aligned(pre, 4)))
         return ESP_EALIGN;
-    if (M > 4) {
-        // larger batches: the two-kernel route through the pre-activation buffer
-        if (!pre)
-            return ESP_EWORKSPACE;
-        const int st = esp_dense_f32(X, W, pre, M, N, K, stream);
-        if (st != ESP_OK)
-            return st;
-        if (N >= (1ll << 31))
-            return ESP_ESHAPE;
-        return esp_bn_sign_pack_f32(pre, thr, sgn, bits, M, (int)N, stream);
-    }
+    if (M > 4)   // larger batches: the matrix-core kernel with the threshold epilogue
+        return dense_mfma_launch(X, W, pre, thr, sgn, bits, M, N, K, as_stream(stream));
     const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
     // 64 neurons per block when that gives every CU a block, else 16; the grid covers every
     // 16-bit piece of the output words, also those beyond N (zeros)

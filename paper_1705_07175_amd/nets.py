@@ -81,10 +81,9 @@ class BinaryMLP:
             esp.bitplane_combine(self.plane_dots, self.wsum0, out=self.pre[0])
             esp.bn_sign_pack(self.pre[0], self.bn[0].thr, self.bn[0].flip, out=self.act[0])
         else:
-            # one kernel up to 4 rows (then pre[0] is written only when asked for), two beyond
-            keep = self.keep_first_pre or self.batch > 4
+            # one kernel; the float pre-activations are written only when asked for
             esp.dense_f32_bn_sign_pack(x, self.w1, self.bn[0].thr, self.bn[0].sgn, out=self.act[0],
-                                       pre=self.pre[0] if keep else None)
+                                       pre=self.pre[0] if self.keep_first_pre else None)
         self._binary_layers()
         return self.pre[-1]
 

@@ -106,7 +106,6 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_conv_f32_bn_sign_pack(p, p, p, p, None, None, 1, 4, 4, 3, 8, 3, 3, 1, 1, None) == -1
     assert lib.esp_bn_fold(None, p, p, p, 1e-4, 4, p, p) == -1
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, None, p, None, 1, 4, 4, None) == -1
-    assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p, None, 5, 4, 4, None) == -4    # M > 4 needs `pre`
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p + 4, None, 1, 4, 4, None) == -2
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p, None, 0, 4, 4, None) == 0
     # fused pool: shapes that cannot hold whole row pairs in a tile are refused up front

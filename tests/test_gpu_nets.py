@@ -99,7 +99,7 @@ def test_mlp_batch1024_sampled_rows(engine):
     # full-size batch on the GPU; the oracle recomputes a sample of the (independent) rows
     layers = synth.mlp_params()
     x = synth.mlp_input(1024)
-    net = nets.BinaryMLP(layers, 1024, EPS, DEV, engine=engine)
+    net = nets.BinaryMLP(layers, 1024, EPS, DEV, engine=engine, keep_first_pre=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
     rows = np.array([0, 1, 63, 64, 511, 777, 1023])
     act0 = oracle.unpack_bits(esp.packed_to_numpy(net.act[0])[rows], 4096)

@@ -548,9 +548,10 @@ def test_conv_f32(B, H, W, C, L2, k, stride, pad):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (2, 100, 50), (3, 64, 31), (4, 130, 784), (1, 65, 4),
-                                   (4, 1000, 1001), (5, 4096, 784), (70, 130, 97), (2, 16390, 64)])
+                                   (4, 1000, 1001), (5, 4096, 784), (70, 130, 97), (2, 16390, 64),
+                                   (64, 4096, 784), (1024, 4096, 784), (300, 70, 130), (65, 33, 36)])
 def test_dense_f32_bn_sign_pack(M, N, K):
-    # M <= 4: one kernel (64 neurons per block); beyond: dense + threshold through `pre`
+    # M <= 4: the streaming kernel (16 or 64 neurons per block); beyond: the matrix-core kernel
     rng = np.random.default_rng(M + 10 * N + 100 * K)
     x = rng.random((M, K), dtype=np.float32)
     w = _pm1(rng, (N, K))
@@ -564,11 +565,7 @@ def test_dense_f32_bn_sign_pack(M, N, K):
     # bits equal the oracle's batch-norm + sign of those same fp32 pre-activations
     want = oracle.pack_bits(oracle.bn_sign(pre.cpu().numpy().astype(np.float64), bnp, synth.BN_EPS))
     assert np.array_equal(esp.packed_to_numpy(bits), want)
-    if M <= 4:
-        assert torch.equal(esp.dense_f32_bn_sign_pack(xd, wd, td, sd), bits)      # without `pre`
-    else:
-        with pytest.raises(esp.EspressoError):
-            esp.dense_f32_bn_sign_pack(xd, wd, td, sd)
+    assert torch.equal(esp.dense_f32_bn_sign_pack(xd, wd, td, sd), bits)      # without `pre`
 
 
 def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
