@@ -15,13 +15,13 @@
 // A 0 bit is -1 throughout, which is also the -1 border of a convolution.  pa and pb are
 // counted once per block by the threads that fetch the packed rows from global memory.
 //
-// Tile: 256 threads = 2 x 2 waves, each wave 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32
-// (v_mfma_scale_f32_32x32x64_f8f6f4), fed from two LDS buffers of packed rows in the same
-// 16-byte k-group layout as the XOR-popcount kernel: stage s + 1 is written while stage s
-// is read, one barrier per stage.  The kernel is templated on the wave arrangement
-// (WM x WN) and on FN, the 32-column blocks per wave.  Measured on an 8192-cube: 128 x 128
-// per wave (FN = 4: accumulators in AGPRs, one wave per SIMD, half the ANDs per MFMA) ran
-// 15 % slower than FN = 2 with two waves per SIMD, so only the latter is instantiated; with
+// Tile: 256 threads = 2 x 2 waves, each wave FM x FN MFMA blocks of 32 x 32
+// (v_mfma_scale_f32_32x32x64_f8f6f4): 128 x 64 per wave (two blocks per CU), or 64 x 64 per
+// wave (three blocks per CU) for products with fewer than 512 of the large tiles.  Operands
+// come from two LDS buffers of packed rows in the same 16-byte k-group layout as the
+// XOR-popcount kernel: stage s + 1 is written while stage s is read, one barrier per stage.
+// Measured on an 8192-cube: 128 x 128 per wave (accumulators in AGPRs, one wave per SIMD,
+// half the ANDs per MFMA) ran 15 % slower than 128 x 64, so it is not instantiated; with
 // the operand ANDs, the popcounts and the epilogue all removed the time did not change, the
 // loads of a stage (global -> registers -> LDS) and the barrier are what the MFMAs wait for.
 #include <type_traits>
@@ -60,8 +60,8 @@ __device__ __forceinline__ v8i encode(const uint4 x)
     return r;
 }
 
-template <int J, int FN>
-__device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&xb)[FN], v16f (&acc)[4][FN])
+template <int J, int FM, int FN>
+__device__ __forceinline__ void mfma_group(const uint4 (&xa)[FM], const uint4 (&xb)[FN], v16f (&acc)[FM][FN])
 {
     constexpr int sc = J == 0 ? kScale2 : (J == 1 ? kScale1 : kScaleHalf);
     v8i b[FN];
@@ -69,7 +69,7 @@ __device__ __forceinline__ void mfma_group(const uint4 (&xa)[4], const uint4 (&x
     for (int g = 0; g < FN; ++g)
         b[g] = encode<J>(xb[g]);
 #pragma unroll
-    for (int f = 0; f < 4; ++f) {
+    for (int f = 0; f < FM; ++f) {
         const v8i a = encode<J>(xa[f]);
 #pragma unroll
         for (int g = 0; g < FN; ++g)
@@ -92,13 +92,13 @@ struct MfmaOut {
                             // and this is log2 of the convolution's output width W2
 };
 
-template <class ASrc, bool VEC16B, bool BITS, int WM, int WN, int FN>
-__global__ __launch_bounds__(256, FN == 4 ? 1 : 2)
+template <class ASrc, bool VEC16B, bool BITS, int WM, int WN, int FM, int FN>
+__global__ __launch_bounds__(256, FM * FN >= 16 ? 1 : (FM * FN >= 8 ? 2 : 3))
 void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const MfmaOut o, int M, int N,
                        int K_true, int row_dw, int tiles_m, int tiles_n, int tiles_per_xcd)
 {
     static_assert(WM * WN == 4, "four waves per block");
-    constexpr int BM = WM * 128, BN = WN * FN * 32, KG = kMfmaKG, NT = 256;
+    constexpr int BM = WM * FM * 32, BN = WN * FN * 32, KG = kMfmaKG, NT = 256;
     constexpr int STAGE_DW = KG * 4;
     // two LDS buffers: stage s + 1 is written while stage s is still being read
     __shared__ uint4 As[2][KG][BM + 1];
@@ -117,7 +117,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         pb_s[i] = 0;
     const int lane = tid % kWave;
     const int wave = tid / kWave;
-    const int wm = (wave / WN) * 128;        // wave's row offset inside the block tile
+    const int wm = (wave / WN) * (FM * 32);  // wave's row offset inside the block tile
     const int wn = (wave % WN) * (FN * 32);  // wave's column offset
 
     // loader: chunk idx = tid + i*NT -> (row idx / KG, k-group idx % KG); NT % KG == 0
@@ -185,9 +185,9 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         }
     }
 
-    v16f acc[4][FN];
+    v16f acc[FM][FN];
 #pragma unroll
-    for (int f = 0; f < 4; ++f)
+    for (int f = 0; f < FM; ++f)
 #pragma unroll
         for (int g = 0; g < FN; ++g)
 #pragma unroll
@@ -207,17 +207,17 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             if ((s * KG + 2 * step) * 4 >= row_dw)
                 continue;                    // both k-groups of this step lie beyond the row
             const int kg = 2 * step + half;
-            uint4 xa[4], xb[FN];
+            uint4 xa[FM], xb[FN];
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
+            for (int f = 0; f < FM; ++f)
                 xa[f] = As[buf][kg][wm + f * 32 + lr];
 #pragma unroll
             for (int g = 0; g < FN; ++g)
                 xb[g] = Bs[buf][kg][wn + g * 32 + lr];
-            mfma_group<0, FN>(xa, xb, acc);
-            mfma_group<1, FN>(xa, xb, acc);
-            mfma_group<2, FN>(xa, xb, acc);
-            mfma_group<3, FN>(xa, xb, acc);
+            mfma_group<0, FM, FN>(xa, xb, acc);
+            mfma_group<1, FM, FN>(xa, xb, acc);
+            mfma_group<2, FM, FN>(xa, xb, acc);
+            mfma_group<3, FM, FN>(xa, xb, acc);
         }
         if (s + 1 < stages)
             commit(buf ^ 1);                 // nobody reads that buffer before the barrier below
@@ -269,7 +269,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         }
         auto rows_to_table = [&](auto exact) {
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
+            for (int f = 0; f < FM; ++f)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[wm + f * 32 + 8 * q + 4 * half]);
@@ -308,7 +308,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         if (o.pool_log2w == 0) {
             __builtin_amdgcn_wave_barrier();     // a wave reads back only what it wrote itself
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < FM / 2; ++h) {     // 32 FM rows per wave, 64 lanes
                 const int rl = wm + h * 64 + lane;
 #pragma unroll
                 for (int w = 0; w < NW; ++w)
@@ -322,7 +322,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         }
     } else {
 #pragma unroll
-        for (int f = 0; f < 4; ++f)
+        for (int f = 0; f < FM; ++f)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int rl = wm + f * 32 + 8 * q + 4 * half;
@@ -344,14 +344,15 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     }
 }
 
-// Block shape in use: 2 x 2 waves of 128 x 64 (see the head of this file).
-struct ShapeA { static constexpr int WM = 2, WN = 2, FN = 2; };
+// Block shapes: 2 x 2 waves of 128 x 64 (two blocks per CU) and 2 x 2 waves of 64 x 64 (three).
+struct ShapeA { static constexpr int WM = 2, WN = 2, FM = 4, FN = 2; };
+struct ShapeS { static constexpr int WM = 2, WN = 2, FM = 2, FN = 2; };
 
 template <class ASrc, bool VEC16B, class S>
 static int launch_mfma_shape(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
                              int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
-    constexpr int BM = S::WM * 128, BN = S::WN * S::FN * 32;
+    constexpr int BM = S::WM * S::FM * 32, BN = S::WN * S::FN * 32;
     const int tiles_m = (int)ceil_div(M, BM);
     const int tiles_n = (int)ceil_div(N, BN);
     const int64_t total = (int64_t)tiles_m * tiles_n;
@@ -360,11 +361,11 @@ static int launch_mfma_shape(const ASrc &asrc, const uint32_t *b, const MfmaOut 
     const int per_xcd = (int)ceil_div(total, kXcd);
     const dim3 grid((unsigned)(per_xcd * kXcd));
     if (o.bits)
-        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true, S::WM, S::WN, S::FN>), grid, dim3(256), 0,
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true, S::WM, S::WN, S::FM, S::FN>), grid, dim3(256), 0,
                            stream, asrc, b, o, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
                            per_xcd);
     else
-        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, false, S::WM, S::WN, S::FN>), grid, dim3(256), 0,
+        hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, false, S::WM, S::WN, S::FM, S::FN>), grid, dim3(256), 0,
                            stream, asrc, b, o, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
                            per_xcd);
     return launch_status();
@@ -374,6 +375,11 @@ template <class ASrc, bool VEC16B>
 static int launch_mfma(const ASrc &asrc, const uint32_t *b, const MfmaOut &o, int64_t M, int64_t N,
                        int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
+    // 256 x 128 blocks when they give every CU its two; otherwise 128 x 128 blocks, three per CU
+    // (measured on the 512-channel convolutions at batch 256: 256 large tiles 14.5 / 21.8 us,
+    // 512 small ones 12.9 / 20.6 us; with 1024 large tiles or more the large shape is faster)
+    if (ceil_div(M, 256) * ceil_div(N, 128) < 512)
+        return launch_mfma_shape<ASrc, VEC16B, ShapeS>(asrc, b, o, M, N, K_true, row_dw, stream);
     return launch_mfma_shape<ASrc, VEC16B, ShapeA>(asrc, b, o, M, N, K_true, row_dw, stream);
 }
 
