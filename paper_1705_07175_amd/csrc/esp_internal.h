@@ -30,7 +30,7 @@ inline int resolve_engine(int e, int64_t M, int64_t N, int64_t K)
     if (e != ESP_ENGINE_AUTO)
         return e;
     const int64_t tiles = ceil_div(M, 256) * ceil_div(N, 128);
-    return (tiles >= 128 && K < (1ll << 24)) ? ESP_ENGINE_MFMA : ESP_ENGINE_XOR_POPCOUNT;
+    return (tiles >= 64 && K < (1ll << 24)) ? ESP_ENGINE_MFMA : ESP_ENGINE_XOR_POPCOUNT;
 }
 
 // Division of a 32-bit unsigned value by a run-time constant, done as a
