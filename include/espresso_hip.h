@@ -325,6 +325,18 @@ int esp_row_sums(const uint64_t *W, int32_t *wsum, int64_t N, int64_t row_words,
 int esp_bitplane_combine(const int32_t *d, const int32_t *wsum, int32_t *y, int64_t outer,
                          int64_t inner, int64_t N, esp_stream stream);
 
+/* ------------------------------------------------------------------------- */
+/* Measurement aid: the in-register ceiling of the inner loop of Eq. 2 (Sec.  */
+/* 4.2, with XOR for XNOR).  Launches `blocks` blocks of 256 lanes; every lane */
+/* runs `iters` rounds of an 8 x 8 register block of v_xor_b32 + accumulating  */
+/* v_bcnt_u32_b32 pairs on values that stay in registers (no memory traffic    */
+/* besides one final store per lane).  sink (device, uint32 [blocks * 256])    */
+/* receives each lane's counter sum; *bop (HOST) receives the number of binary */
+/* operations of the launch (64 per pair), so that bop / time is comparable    */
+/* with esp_bgemm's 2*M*N*K / time.  blocks, iters in [1, 2^20].               */
+/* ------------------------------------------------------------------------- */
+int esp_xor_popcount_probe(uint32_t *sink, int blocks, int iters, int64_t *bop, esp_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,6 +30,7 @@ EXPORTS = (
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
     "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2", "esp_dense_f32_bn_sign_pack",
+    "esp_xor_popcount_probe",
 )
 
 _lib = None
@@ -80,6 +81,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_pool2_fusable.argtypes = [i32] * 7
         l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
         l.esp_dense_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        l.esp_xor_popcount_probe.argtypes = [vp, i32, i32, vp, vp]
         l.esp_version.argtypes = []
         for name in EXPORTS:
             # without a prototype ctypes would pass pointers as 32-bit ints: refuse to load
@@ -472,6 +474,17 @@ def bitplane_combine(d: torch.Tensor, wsum: torch.Tensor, out: torch.Tensor | No
     _check(lib().esp_bitplane_combine(pd, _dev(wsum, torch.int32, "wsum"), _dev(out, torch.int32, "out"),
                                       outer, inner, N, _stream()), "esp_bitplane_combine")
     return out
+
+
+def xor_popcount_probe(sink: torch.Tensor, blocks: int, iters: int) -> int:
+    """``esp_xor_popcount_probe``: launch the in-register xor + popcount loop; returns the number
+    of binary operations the launch performs.  ``sink``: uint32/int32 [blocks * 256] on the device."""
+    if sink.numel() < blocks * 256:
+        raise ValueError("sink must hold blocks * 256 values")
+    bop = ctypes.c_int64(0)
+    _check(lib().esp_xor_popcount_probe(_dev(sink, torch.int32, "sink"), int(blocks), int(iters),
+                                        ctypes.addressof(bop), _stream()), "esp_xor_popcount_probe")
+    return int(bop.value)
 
 
 # ------------------------------------------------------------------ host <-> device helpers

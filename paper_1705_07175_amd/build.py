@@ -26,6 +26,7 @@ SOURCES = (
     ("conv.hip", ()),
     ("float_layers.hip", ()),
     ("bitplane.hip", ()),
+    ("probe.hip", ()),
     ("host.cpp", ("-ffp-contract=off",)),
 )
 

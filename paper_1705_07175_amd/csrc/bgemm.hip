@@ -174,6 +174,24 @@ struct StoreSignBits {
     }
 };
 
+// acc += popcount(a XOR b) over the four dwords of two 16-byte chunks: the inner step of Eq. 2.
+// Written out as instructions because their order decides the rate on gfx950: v_xor_b32 issues
+// in half the time of v_bcnt_u32_b32, but two waves that share a SIMD only overlap that way when
+// a scalar instruction separates the pairs (measured on registers only, two waves per SIMD:
+// xor, bcnt back to back 1.24 Pbop/s; one s_nop per pair 1.63; two, or one per two pairs, 1.2).
+// The compiler places one more s_nop between consecutive asm statements, which is the
+// separator of the fourth pair.
+__device__ __forceinline__ void xor_popc_acc4(int &acc, const uint4 &a, const uint4 &b)
+{
+    uint32_t t;
+    asm volatile("v_xor_b32 %0, %2, %6\n\tv_bcnt_u32_b32 %1, %0, %1\n\ts_nop 0\n\t"
+                 "v_xor_b32 %0, %3, %7\n\tv_bcnt_u32_b32 %1, %0, %1\n\ts_nop 0\n\t"
+                 "v_xor_b32 %0, %4, %8\n\tv_bcnt_u32_b32 %1, %0, %1\n\ts_nop 0\n\t"
+                 "v_xor_b32 %0, %5, %9\n\tv_bcnt_u32_b32 %1, %0, %1"
+                 : "=&v"(t), "+v"(acc)
+                 : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w));
+}
+
 template <int BM, int BN, int TM, int TN, class ASrc, bool VEC16B, bool BITS>
 __global__ __launch_bounds__((BM / TM) * (BN / TN))
 void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const StoreDots dots,
@@ -280,10 +298,7 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    acc[i][j] += __popc(a[i].x ^ b[j].x);
-                    acc[i][j] += __popc(a[i].y ^ b[j].y);
-                    acc[i][j] += __popc(a[i].z ^ b[j].z);
-                    acc[i][j] += __popc(a[i].w ^ b[j].w);
+                    xor_popc_acc4(acc[i][j], a[i], b[j]);
                 }
         }
         __syncthreads();

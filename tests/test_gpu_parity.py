@@ -613,3 +613,22 @@ def test_conv_f32_bn_sign_pack_fused_equals_two_step():
         assert np.array_equal(esp.packed_to_numpy(fused), want)
         if (C, k, stride) == (3, 3, 1):
             assert torch.equal(esp.conv_f32_bn_sign_pack(xd, fd, td, sd, stride, pad), two)
+
+
+def test_xor_popcount_probe_counts_what_it_claims():
+    # the measurement aid must really execute the pairs it reports: every lane's counter sum is
+    # iters * sum_ij popcount(a_i ^ b_j) for the lane's seeded register values
+    blocks, iters = 3, 5
+    sink = torch.zeros(blocks * 256, dtype=torch.int32, device=DEV)
+    bop = esp.xor_popcount_probe(sink, blocks, iters)
+    assert bop == blocks * 256 * iters * 64 * 64
+    seed = np.arange(blocks * 256, dtype=np.uint64)
+    mask = np.uint64(0xffffffff)
+    a = [(seed * np.uint64(2654435761) + np.uint64(0x9e3779b9 * (i + 1))) & mask for i in range(8)]
+    b = [(seed * np.uint64(40503) + np.uint64(0x85ebca6b * (j + 1))) & mask for j in range(8)]
+    want = np.zeros(blocks * 256, dtype=np.int64)
+    for ai in a:
+        for bj in b:
+            x = ai ^ bj
+            want += np.array([bin(int(v)).count("1") for v in x])
+    assert np.array_equal(sink.cpu().numpy().astype(np.int64), want * iters)
