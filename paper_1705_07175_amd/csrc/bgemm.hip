@@ -6,7 +6,9 @@
 //    BN x 1024-bit slabs of the packed rows in LDS as 16-byte k-groups, every lane
 //    keeps a TM x TN tile of int32 mismatch counters in registers and runs a pure
 //    v_xor_b32 / v_bcnt_u32_b32 (accumulating popcount) inner loop on 32-bit halves
-//    of the words.  The paper's own design (shared-memory tiles + register blocking,
+//    of the words.  Two LDS stage buffers (one barrier per stage), global loads one
+//    stage ahead, LDS operand reads one k-group ahead: a wave that waits leaves its
+//    SIMD to the one other wave, which runs at its own fixed pace.  The paper's own design (shared-memory tiles + register blocking,
 //    Sec. 5.2 "Efficient Matrix multiplication") is kept; tile shapes, the LDS
 //    layout and the block order are chosen for 64-wide wavefronts and 8 XCDs.
 //    The A operand comes either from a packed matrix or, for convolutions, straight
@@ -204,8 +206,10 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
     static_assert(TN % 4 == 0, "columns are owned in groups of four");
     static_assert((BM * kKG) % NT == 0 && (BN * kKG) % NT == 0, "loader shape");
 
-    __shared__ uint4 As[kKG][BM + 1];
-    __shared__ uint4 Bs[kKG][BN + 1];
+    // two stage buffers: stage s + 1 is written while other waves still read stage s, so one
+    // barrier per stage is enough
+    __shared__ uint4 As[2][kKG][BM + 1];
+    __shared__ uint4 Bs[2][kKG][BN + 1];
 
     int tm, tn;
     if (!block_to_tile(tiles_m, tiles_n, tiles_per_xcd, &tm, &tn))
@@ -218,43 +222,47 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
     const int ty = tid / TX;
 
     // loader: chunk idx = tid + i*NT covers (row idx / kKG, k-group idx % kKG); NT is a
-    // multiple of kKG, so a thread always loads the same k-group of its rows
+    // multiple of kKG, so a thread always loads the same k-group of its rows.  Loads are
+    // branch-free (clamped rows, masked K tail): rows beyond M or N compute values that are
+    // never stored.
     constexpr int A_CH = BM * kKG / NT;
     constexpr int B_CH = BN * kKG / NT;
     const int kg_mine = tid % kKG;
     typename ASrc::Row arow[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-        arow[i] = asrc.row(m0 + (tid + i * NT) / kKG);
+        arow[i] = asrc.row_nb(m0 + (tid + i * NT) / kKG);
     const uint32_t *brow[B_CH];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int n = n0 + (tid + i * NT) / kKG;
-        brow[i] = n < N ? B + (int64_t)n * row_dw : nullptr;
-    }
+    for (int i = 0; i < B_CH; ++i)
+        brow[i] = B + (int64_t)min(n0 + (tid + i * NT) / kKG, N - 1) * row_dw;
     uint4 pa[A_CH], pb[B_CH];
+    bool ka[A_CH], kb;     // whether a chunk counts; applied when it moves to LDS
 
     auto prefetch = [&](int stage) {
         const int kd = stage * kStageDw + kg_mine * 4;
         const typename ASrc::Step st = asrc.step(kd);
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            pa[i] = asrc.fetch(arow[i], st, kd);
+        for (int i = 0; i < A_CH; ++i) {
+            pa[i] = asrc.fetch_raw(arow[i], st, kd);
+            ka[i] = asrc.keep(arow[i], st, kd);
+        }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i)
-            pb[i] = brow[i] ? load_chunk<VEC16B>(brow[i], kd, row_dw) : zero4();
+            pb[i] = load_chunk_raw<VEC16B>(brow[i], kd, row_dw);
+        kb = kd < row_dw;
     };
 
-    auto commit = [&]() {
+    auto commit = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i)
-            As[kg_mine][(tid + i * NT) / kKG] = pa[i];
+            As[buf][kg_mine][(tid + i * NT) / kKG] = keep4(pa[i], ka[i]);
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             const int nl = (tid + i * NT) / kKG;
             // column nl is register column j of lane tx: nl = (j/4)*(4*TX) + tx*4 + j%4
             const int j = (nl / (4 * TX)) * 4 + nl % 4;
-            Bs[kg_mine][j * TX + (nl % (4 * TX)) / 4] = pb[i];
+            Bs[buf][kg_mine][j * TX + (nl % (4 * TX)) / 4] = keep4(pb[i], kb);
         }
     };
 
@@ -278,29 +286,59 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
 
     const int stages = (row_dw + kStageDw - 1) / kStageDw;
     prefetch(0);
+    commit(0);
+    __syncthreads();
     for (int s = 0; s < stages; ++s) {
-        commit();
-        __syncthreads();
+        const int buf = s & 1;
         if (s + 1 < stages)
             prefetch(s + 1);
         const int left_dw = row_dw - s * kStageDw;
         const int kgs = left_dw >= kStageDw ? kKG : (left_dw + 3) / 4;
-#pragma unroll 2
-        for (int kg = 0; kg < kgs; ++kg) {
-            uint4 a[TM], b[TN];
+        // Operands travel LDS -> registers one k-group ahead of their use: while k-group kg is
+        // counted, the B chunks and the first A chunk of k-group kg + 1 arrive, and the other
+        // A chunks of kg (issued at its start) are not needed before its second row of
+        // counters.  A wave that waits for LDS leaves its SIMD to the other wave, which cannot
+        // make up for it, so no counter should ever wait.  Two register sets alternate.
+        auto kgroup = [&](int kg, int kg_next, const uint4 &a0, const uint4 (&b)[TN], uint4 &a0_next,
+                          uint4 (&b_next)[TN]) {
+            uint4 a[TM];
+            a[0] = a0;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = As[kg][ty + TY * i];
+            for (int i = 1; i < TM; ++i)
+                a[i] = As[buf][kg][ty + TY * i];
+            a0_next = As[buf][kg_next][ty];
+            // first row of counters on operands that arrived during the previous k-group; the
+            // reads of b_next are issued behind it so that no more than 15 reads are ever
+            // outstanding (the wait counter cannot express more, and would wait too early)
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                b[j] = Bs[kg][j * TX + tx];
+                xor_popc_acc4(acc[0][j], a[0], b[j]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j)
+                b_next[j] = Bs[buf][kg_next][j * TX + tx];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
+            for (int i = 1; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
                     xor_popc_acc4(acc[i][j], a[i], b[j]);
-                }
+        };
+        uint4 a0_even, b_even[TN], a0_odd, b_odd[TN];
+        a0_even = As[buf][0][ty];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            b_even[j] = Bs[buf][0][j * TX + tx];
+        int kg = 0;
+        for (; kg + 1 < kgs; kg += 2) {
+            kgroup(kg, kg + 1, a0_even, b_even, a0_odd, b_odd);
+            kgroup(kg + 1, min(kg + 2, kKG - 1), a0_odd, b_odd, a0_even, b_even);
         }
+        if (kg < kgs)
+            kgroup(kg, kg, a0_even, b_even, a0_odd, b_odd);
+        if (s + 1 < stages)
+            commit(buf ^ 1);
         __syncthreads();
     }
 
@@ -326,7 +364,7 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
             // 2x2 max-pool of +-1 values = OR of the sign bits: the tile's words meet in LDS
             // (the A slab is free after the last stage) and every pooled word ORs its four sources
             constexpr int WPT = BN / 64;
-            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0]);
+            uint64_t *wt = reinterpret_cast<uint64_t *>(&As[0][0][0]);
             if (lw.have)
                 wt[lw.rl * WPT + lw.wl] = word;
             __syncthreads();

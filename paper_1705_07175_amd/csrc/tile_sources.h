@@ -63,6 +63,17 @@ __device__ __forceinline__ uint4 load_chunk_nb(const uint32_t *__restrict__ p, i
     return make_uint4(lo.x & m0, lo.y & m0, hi.x & m1, hi.y & m1);
 }
 
+// load_chunk_nb without the final mask where a single mask covers the chunk (VEC16: the caller
+// applies keep4(v, kd < row_dw) when it uses the data, so that nothing waits for the load at
+// the point of issue); the 8-byte path masks its halves at once.
+template <bool VEC16>
+__device__ __forceinline__ uint4 load_chunk_raw(const uint32_t *__restrict__ p, int kd, int row_dw)
+{
+    if (VEC16)
+        return *reinterpret_cast<const uint4 *>(p + min(kd, row_dw - 4));
+    return load_chunk_nb<false>(p, kd, row_dw);
+}
+
 // ---- A operand: rows of a packed matrix ------------------------------------------
 template <bool VEC16>
 struct MatrixA {
@@ -86,6 +97,14 @@ struct MatrixA {
     {
         return load_chunk_nb<VEC16>(r.p, kd, row_dw);
     }
+    // the same in two parts, so that the mask can wait until the data is used: fetch_raw reads
+    // the clamped address, keep() says whether the chunk counts (keep4(fetch_raw, keep) ==
+    // fetch_nb)
+    __device__ __forceinline__ uint4 fetch_raw(const Row &r, const Step &, int kd) const
+    {
+        return load_chunk_raw<VEC16>(r.p, kd, row_dw);
+    }
+    __device__ __forceinline__ bool keep(const Row &, const Step &, int kd) const { return kd < row_dw; }
 };
 
 // ---- A operand: the lowered matrix of a convolution, gathered on the fly ----------
@@ -132,6 +151,16 @@ struct ConvA {
         const bool inside = kd < row_dw && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
         const int yc = min(max(y, 0), H - 1), xc = min(max(x, 0), W - 1);
         return keep4(*reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)yc * W + xc) * cdw + s.c), inside);
+    }
+    __device__ __forceinline__ uint4 fetch_raw(const Row &r, const Step &s, int kd) const
+    {
+        const int yc = min(max(r.y0 + s.dy, 0), H - 1), xc = min(max(r.x0 + s.dx, 0), W - 1);
+        return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)yc * W + xc) * cdw + s.c);
+    }
+    __device__ __forceinline__ bool keep(const Row &r, const Step &s, int kd) const
+    {
+        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
+        return kd < row_dw && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
     }
 };
 
