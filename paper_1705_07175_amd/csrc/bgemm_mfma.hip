@@ -141,26 +141,33 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
         nb[i] = 0;
+    bool ka[A_CH], kb_keep;   // whether a fetched chunk counts; applied when it moves to LDS, so
+                              // that nothing waits for a load at the point of issue
     auto prefetch = [&](int stage) {
         const int kd = stage * STAGE_DW + kg_mine * 4;
         const typename ASrc::Step st = asrc.step(kd);
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            pa[i] = asrc.fetch_nb(arow[i], st, kd);
+        for (int i = 0; i < A_CH; ++i) {
+            pa[i] = asrc.fetch_raw(arow[i], st, kd);
+            ka[i] = asrc.keep(arow[i], st, kd);
+        }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i)
-            pb[i] = load_chunk_nb<VEC16B>(brow[i], kd, row_dw);
+            pb[i] = load_chunk_raw<VEC16B>(brow[i], kd, row_dw);
+        kb_keep = kd < row_dw;
     };
     auto commit = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            As[buf][kg_mine][(tid + i * NT) / KG] = pa[i];
-            na[i] += popc4(pa[i]);
+            const uint4 v = keep4(pa[i], ka[i]);
+            As[buf][kg_mine][(tid + i * NT) / KG] = v;
+            na[i] += popc4(v);
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            Bs[buf][kg_mine][(tid + i * NT) / KG] = pb[i];
-            nb[i] += popc4(pb[i]);
+            const uint4 v = keep4(pb[i], kb_keep);
+            Bs[buf][kg_mine][(tid + i * NT) / KG] = v;
+            nb[i] += popc4(v);
         }
     };
 
