@@ -138,6 +138,22 @@ def test_bgemm_large_tile_path_full():
     assert np.array_equal(got, oracle.dense_pm1(a, b))
 
 
+# every length of the last K stage (1 to 8 k-groups of 128 bits, handled two at a time with an odd
+# one at the end), an odd number of words per row (8-byte loads) and a K that is not a multiple of
+# 64, on each of the three tile shapes
+@pytest.mark.parametrize("M,N,Ks", [
+    (130, 70, (1088, 1152, 1280, 1344, 1472, 1600, 1728, 1856, 1984, 2048, 2112, 1100, 960, 64)),
+    (1100, 1100, (1152, 1280, 1472, 1728, 1984, 2112, 1100)),
+    (2900, 2950, (1152, 1344, 1600, 2112)),
+])
+def test_bgemm_tile_k_tails(M, N, Ks):
+    for K in Ks:
+        rng = np.random.default_rng(M + 31 * K)
+        a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+        got = esp.bgemm(_packed_dev(a), _packed_dev(b), K).cpu().numpy()
+        assert np.array_equal(got, oracle.dense_pm1(a, b)), K
+
+
 def _check_sampled(a, b, c, rng, nrows=6, ncols=6):
     """Sampled rows and columns bit-exact plus the full-matrix checksum identities
     sum_n C[m][n] = a_m . (sum_n b_n) and its column analogue, which touch every output."""
