@@ -90,6 +90,7 @@ struct MfmaOut {
     int Nw;
     int pool_log2w;         // 0: no pooling; else bits is [M/4][Nw] behind a fused 2x2 max-pool
                             // and this is log2 of the convolution's output width W2
+    int vec_store;          // C is 16-byte aligned and N a multiple of 4: 16-byte stores
 };
 
 template <class ASrc, bool VEC16B, bool BITS, int WM, int WN, int FM, int FN>
@@ -327,6 +328,35 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             __syncthreads();
             pool_tile_store<BM, WPT, NT>(wt, o.bits, m0, n0, M, o.Nw, o.pool_log2w, tid);
         }
+    } else if (o.vec_store) {
+        // int32 out, 16-byte stores: a 32 x 32 block leaves the accumulators as lane -> column,
+        // register -> row; it is turned through a 4 KB LDS patch of the wave's own (the A slabs
+        // are free by now) so that 8 lanes write one 128-byte row segment with one store each.
+        int *patch = reinterpret_cast<int *>(&As[0][0][0]) + wave * 1024;
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+            for (int g = 0; g < FN; ++g) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[wm + f * 32 + 8 * q + 4 * half]);
+                    const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        patch[(8 * q + 4 * half + t) * 32 + lr] = 4 * (int)acc[f][g][4 * q + t] + kb[g] - 2 * pav[t];
+                }
+                __builtin_amdgcn_wave_barrier();
+                const int col = n0 + wn + g * 32 + 4 * (lane % 8);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int r = lane / 8 + 8 * k;
+                    const int4 v = *reinterpret_cast<const int4 *>(&patch[r * 32 + 4 * (lane % 8)]);
+                    const int row = m0 + wm + f * 32 + r;
+                    if (row < M && col < N)     // N % 4 == 0: the four columns are inside together
+                        *reinterpret_cast<int4 *>(&o.C[(int64_t)row * N + col]) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
     } else {
 #pragma unroll
         for (int f = 0; f < FM; ++f)
@@ -398,7 +428,7 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
         return ESP_OK;
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29) || K_true >= kMaxMfmaK)
         return ESP_ESHAPE;
-    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64), 0};
+    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64), 0, (N % 4 == 0) && aligned(C, 16)};
     const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
     const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
@@ -419,7 +449,7 @@ int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, 
     if (M >= (1ll << 31) || K_true >= kMaxMfmaK || (int64_t)B * H * W * (C / 32) >= (1ll << 40))
         return ESP_ESHAPE;
     const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
-    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64), pool_log2w};
+    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64), pool_log2w, (L2 % 4 == 0) && aligned(C_out, 16)};
     return launch_mfma<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2, K_true, a.row_dw,
                                     stream);
 }
