@@ -90,11 +90,78 @@ void rowbits_kernel(const typename Op::in_t *__restrict__ x, uint64_t *__restric
     }
 }
 
+// The same when C is a multiple of 64: rows are then whole words and, rows being contiguous,
+// the array is one flat run of 64-value words.  A wave task is 16 consecutive words, so its 16
+// loads cover 4 KB of contiguous memory and its 16 output words are one 128-byte store (the
+// column-per-wave shape above walks 16 rows that lie C * 4 bytes apart and scatters 8-byte
+// stores over them).  PERIODIC: Cw divides 16, so the channel of word j of a task is the same
+// in every task and the per-channel state is fetched once per wave; otherwise Cw >= 16 and the
+// word position inside the row is carried along (one wrap per step at most).
+template <class Op, bool PERIODIC>
+__global__ __launch_bounds__(256)
+void rowbits_flat_kernel(const typename Op::in_t *__restrict__ x, uint64_t *__restrict__ out,
+                         int Cw, int64_t words, int64_t tasks, Op op)
+{
+    using in_t = typename Op::in_t;
+    const int lane = threadIdx.x % kWave;
+    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    typename Op::Lane fixed[PERIODIC ? kRows : 1];
+    if (PERIODIC) {
+#pragma unroll
+        for (int j = 0; j < kRows; ++j)
+            fixed[j] = op.lane_state((j % Cw) * 64 + lane, true);
+    }
+    int w0 = (int)((wave0 * kRows) % Cw);               // word position of the task's first word
+    const int w_step = (int)((nwaves * kRows) % Cw);
+    for (int64_t task = wave0; task < tasks; task += nwaves, w0 = w0 + w_step >= Cw ? w0 + w_step - Cw : w0 + w_step) {
+        const int64_t g0 = task * kRows;
+        const in_t *p = x + g0 * 64 + lane;
+        in_t v[kRows];
+        if (g0 + kRows <= words) {
+#pragma unroll
+            for (int j = 0; j < kRows; ++j)
+                v[j] = p[j * 64];
+        } else {
+#pragma unroll
+            for (int j = 0; j < kRows; ++j)
+                v[j] = g0 + j < words ? p[j * 64] : in_t(0);
+        }
+        uint64_t mine = 0;
+#pragma unroll
+        for (int j = 0; j < kRows; ++j) {
+            uint64_t word;
+            if (PERIODIC)
+                word = __ballot(op.bit(v[j], fixed[j]));
+            else
+                word = __ballot(op.bit(v[j], op.lane_state((w0 + j >= Cw ? w0 + j - Cw : w0 + j) * 64 + lane, true)));
+            if (lane == j)
+                mine = word;
+        }
+        if (lane < kRows && g0 + lane < words) {
+            const int wl = PERIODIC ? lane % Cw : (w0 + lane >= Cw ? w0 + lane - Cw : w0 + lane);
+            out[g0 + lane] = op.post(mine, wl);
+        }
+    }
+}
+
 template <class Op>
 static int launch_rowbits(const typename Op::in_t *x, uint64_t *out, int64_t rows, int64_t C,
                           Op op, hipStream_t stream)
 {
     const int64_t Cw = ceil_div(C, 64);
+    if (C % 64 == 0 && (kRows % Cw == 0 || Cw >= kRows)) {
+        const int64_t words = rows * Cw;
+        const int64_t tasks = ceil_div(words, kRows);
+        const dim3 grid(grid_for(tasks, 4));
+        if (kRows % Cw == 0)
+            hipLaunchKernelGGL((rowbits_flat_kernel<Op, true>), grid, dim3(256), 0, stream, x, out, (int)Cw, words,
+                               tasks, op);
+        else
+            hipLaunchKernelGGL((rowbits_flat_kernel<Op, false>), grid, dim3(256), 0, stream, x, out, (int)Cw, words,
+                               tasks, op);
+        return launch_status();
+    }
     const int64_t tasks = Cw * ceil_div(rows, kRows);
     const unsigned grid = grid_for(tasks, 4);
     hipLaunchKernelGGL((rowbits_kernel<Op>), dim3(grid), dim3(256), 0, stream, x, out, rows, (int)C,
