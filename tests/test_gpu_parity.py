@@ -39,7 +39,8 @@ def _packed_dev(pm1):
 
 # ------------------------------------------------------------------------------ pack
 @pytest.mark.parametrize("rows,k", [(1, 1), (1, 64), (3, 63), (5, 65), (17, 200), (64, 1024),
-                                    (1000, 1000), (33, 4096), (2500, 128), (1, 16384)])
+                                    (1000, 1000), (33, 4096), (2500, 128), (1, 16384), (37, 1280), (9, 1088),
+                                    (5, 192), (3, 64)])
 def test_pack_f32(rows, k):
     rng = np.random.default_rng(rows * 100003 + k)
     x = rng.standard_normal((rows, k)).astype(np.float32)
@@ -306,8 +307,12 @@ def test_config2_conv_bn_sign_pack_chain():
 
 
 # ------------------------------------------------------------------------------ bn_sign_pack
+# C a multiple of 64 takes the flat-word kernel: with the per-channel state fetched once (words per
+# row dividing 16: 64, 128, 1024), carried along (1280 = 20 words: a task wraps inside a row; 1536),
+# or the column-per-wave kernel (192 = 3 words; ragged C); row counts leave a partial last task
 @pytest.mark.parametrize("rows,C,K", [(1, 64, 64), (5, 70, 300), (64, 4096, 4096), (1000, 128, 1152),
-                                      (17, 1024, 8192), (3, 10, 1024)])
+                                      (17, 1024, 8192), (3, 10, 1024), (37, 1280, 2000), (11, 1536, 500),
+                                      (50, 192, 900), (3, 128, 128), (7, 256, 700)])
 def test_bn_sign_pack(rows, C, K):
     rng = np.random.default_rng(rows + C)
     bnp = synth.bn_params(rng, C)
