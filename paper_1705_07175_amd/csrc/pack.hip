@@ -4,16 +4,18 @@
 // real-valued first layer (batch-norm folded to a float threshold on the host).
 //
 // All three are one pass over a [rows][C] array that emits one bit per element, so they
-// share one bandwidth-oriented skeleton: a wave owns one 64-channel word column w and
-// kRows consecutive rows; lane l loads element (r, 64*w + l) for each of those rows
-// (every load instruction of the wave is one contiguous 256-byte segment, kRows of them
-// in flight), the comparison writes its 64-lane result mask straight into a scalar
-// register pair, which IS the packed word, and lanes 0..kRows-1 store one word each.
+// share one bandwidth-oriented skeleton: lane l of a wave loads the element of bit
+// position l of a word (every load instruction of the wave is one contiguous 256-byte
+// segment, kRows of them in flight), the comparison writes its 64-lane result mask
+// straight into a scalar register pair, which IS the packed word, and lanes 0..kRows-1
+// store one word each.  Two task shapes: kRows consecutive words of the flat array when
+// C is a multiple of 64 (rowbits_flat_kernel), one word column over kRows consecutive
+// rows otherwise (rowbits_kernel).
 #include "esp_internal.h"
 
 namespace esp {
 
-constexpr int kRows = 16; // rows per wave task = independent loads in flight per lane
+constexpr int kRows = 16; // words per wave task = independent loads in flight per lane
 
 struct SignF32 {
     using in_t = float;
