@@ -371,6 +371,7 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
     static_assert(NB == 1 || NB == 4, "one block per wave (32-bit output pieces) or whole words");
     __shared__ float win_all[4][WIN + 2];          // + a zero slot for the padding k = 27, + scratch
     __shared__ __align__(16) uint32_t word_all[4][PIX * NB];   // [pixel][block] mask halves
+    __shared__ float filt_s[NB * 32 * T];          // the filters of one channel group, [channel][k]
 
     const int lane = threadIdx.x % kWave;
     // the wave index and everything derived from it (the task decomposition) stay in scalar registers
@@ -379,6 +380,17 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
     float *win = win_all[wave];
     if (lane == 0)
         win[WIN] = 0.0f;
+
+    // The filters of the channel group of the block's first task travel through LDS: read
+    // per lane they are a gather with a stride of 27 floats (32 cache lines per load).  A wave
+    // that later moves on to another group gathers them directly.
+    const int cg_staged = (blockIdx.x * (blockDim.x / kWave)) / rows_strips;
+    {
+        const int64_t base = (int64_t)cg_staged * NB * 32 * T;
+        for (int i = threadIdx.x; i < NB * 32 * T; i += blockDim.x)
+            filt_s[i] = base + i < (int64_t)L2 * T ? filt[base + i] : 0.0f;
+        __syncthreads();
+    }
 
     // window element i = lane + 64 q of a strip: row wr, pixel wx, offset wo from the window's
     // first element in the image (i beyond the window: a row that is never inside the image)
@@ -449,12 +461,19 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
                     sg[nb] = 1.0f;
                     th[nb] = __builtin_inff();         // beyond L2: bit 0
                 }
+                float wv[KS];
+                if (cg == cg_staged) {                // wave-uniform
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const int k = 2 * s + half;
-                    const float wv = filt[(int64_t)l2c * T + (k < T ? k : 0)];
-                    bw[nb][s] = keep_if(sg[nb] * wv, ok && k < T);
+                    for (int s = 0; s < KS; ++s)
+                        wv[s] = filt_s[(nb * 32 + lr) * T + min(2 * s + half, T - 1)];
+                } else {
+#pragma unroll
+                    for (int s = 0; s < KS; ++s)
+                        wv[s] = filt[(int64_t)l2c * T + min(2 * s + half, T - 1)];
                 }
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    bw[nb][s] = keep_if(sg[nb] * wv[s], ok && 2 * s + half < T);
             }
         }
 
