@@ -426,6 +426,8 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
     // contiguous runs of the image; 32-bit offsets from the image's first element
     // (H * W * 3 < 2^31, checked by the host).
     float wv_[kTrips];
+    bool winb_[kTrips];    // inside the image; applied when the value moves to LDS, so that
+                           // nothing waits for the loads where they are issued
     auto fetch_window = [&](int task) {
         const int rs = task % rows_strips;
         const int bm = rs / strips;
@@ -436,7 +438,8 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
 #pragma unroll
         for (int q = 0; q < kTrips; ++q) {
             const bool inb = (unsigned)(y0 + wr[q]) < (unsigned)H && (unsigned)(x0 + wx[q]) < (unsigned)W;
-            wv_[q] = keep_if(img[inb ? first + wo[q] : 0], inb);
+            wv_[q] = img[inb ? first + wo[q] : 0];
+            winb_[q] = inb;
         }
     };
     if (task0 < tasks)
@@ -480,7 +483,7 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int q = 0; q < kTrips; ++q)
-            win[wdst[q]] = wv_[q];
+            win[wdst[q]] = keep_if(wv_[q], winb_[q]);
         __builtin_amdgcn_wave_barrier();   // LDS operations of one wave complete in order
         if (task + nwaves < tasks)
             fetch_window(task + nwaves);
