@@ -11,35 +11,9 @@ namespace esp {
 constexpr int kXcd = 8;       // XCDs (one L2 each); blocks are dealt to them round-robin
 constexpr int kGroupM = 8;    // tile rows walked together so A and B slabs stay in one L2
 
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
-
-// 16 bytes of row `p` starting at dword kd of a row that is row_dw dwords long.
-template <bool VEC16>
-__device__ __forceinline__ uint4 load_chunk(const uint32_t *__restrict__ p, int kd, int row_dw)
-{
-    uint4 v = zero4();
-    if (VEC16) {
-        if (kd < row_dw)
-            v = *reinterpret_cast<const uint4 *>(p + kd);
-    } else {
-        if (kd < row_dw) {
-            const uint2 lo = *reinterpret_cast<const uint2 *>(p + kd);
-            v.x = lo.x;
-            v.y = lo.y;
-        }
-        if (kd + 2 < row_dw) {
-            const uint2 hi = *reinterpret_cast<const uint2 *>(p + kd + 2);
-            v.z = hi.x;
-            v.w = hi.y;
-        }
-    }
-    return v;
-}
-
-// v with every bit cleared unless keep.  The branch-free fetch_nb variants below load from a
+// v with every bit cleared unless keep.  All loaders here are branch-free: they read from a
 // clamped, always valid address and mask the result, so that a loader's independent loads are
-// issued back to back instead of each inside its own branch (used where the loads of a stage
-// must not hold up the matrix cores; the plain variants cost fewer vector instructions).
+// issued back to back instead of each inside its own branch.
 __device__ __forceinline__ uint4 keep4(uint4 v, bool keep)
 {
     const uint32_t m = keep ? 0xffffffffu : 0u;
@@ -81,17 +55,9 @@ struct MatrixA {
     int rows;    // M
     int row_dw;  // dwords per row
     struct Row { const uint32_t *p; };
-    __device__ __forceinline__ Row row(int r) const
-    {
-        return Row{r < rows ? base + (int64_t)r * row_dw : nullptr};
-    }
     struct Step {};
     __device__ __forceinline__ Step step(int /*kd*/) const { return Step{}; }
-    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &, int kd) const
-    {
-        return r.p ? load_chunk<VEC16>(r.p, kd, row_dw) : zero4();
-    }
-    // branch-free: rows beyond the matrix read the last row (their results are never stored)
+    // rows beyond the matrix read the last row (their results are never stored)
     __device__ __forceinline__ Row row_nb(int r) const { return Row{base + (int64_t)min(r, rows - 1) * row_dw}; }
     __device__ __forceinline__ uint4 fetch_nb(const Row &r, const Step &, int kd) const
     {
@@ -118,11 +84,11 @@ struct ConvA {
     int row_dw;  // kh*kw*cdw
     int H, W, cdw, stride, pad;
     FastDiv d_w2, d_h2, d_cdw, d_kw;
-    struct Row { int64_t img; int y0, x0; };   // img < 0: row beyond M
-    __device__ __forceinline__ Row row(int r) const
+    struct Row { int64_t img; int y0, x0; };
+    // rows beyond M read the last row (their results are never stored)
+    __device__ __forceinline__ Row row_nb(int r0) const
     {
-        if (r >= rows)
-            return Row{-1, 0, 0};
+        const int r = min(r0, rows - 1);
         const uint32_t bm = fd_div((uint32_t)r, d_w2);
         const uint32_t n = (uint32_t)r - bm * d_w2.div;
         const uint32_t b = fd_div(bm, d_h2);
@@ -136,15 +102,7 @@ struct ConvA {
         const uint32_t dy = fd_div(tap, d_kw);
         return Step{(int)dy, (int)(tap - dy * d_kw.div), (int)((uint32_t)kd - tap * d_cdw.div)};
     }
-    __device__ __forceinline__ uint4 fetch(const Row &r, const Step &s, int kd) const
-    {
-        const int y = r.y0 + s.dy, x = r.x0 + s.dx;
-        if (r.img < 0 || kd >= row_dw || y < 0 || y >= H || x < 0 || x >= W)
-            return zero4();
-        return *reinterpret_cast<const uint4 *>(in + (r.img + (int64_t)y * W + x) * cdw + s.c);
-    }
-    // branch-free: the pixel is clamped into the image, the border and the K tail are masked
-    __device__ __forceinline__ Row row_nb(int r) const { return row(min(r, rows - 1)); }
+    // the pixel is clamped into the image, the border and the K tail are masked
     __device__ __forceinline__ uint4 fetch_nb(const Row &r, const Step &s, int kd) const
     {
         const int y = r.y0 + s.dy, x = r.x0 + s.dx;
