@@ -584,7 +584,7 @@ template <> struct Chunk<false> {
     static __device__ __forceinline__ uint2 zero() { return make_uint2(0u, 0u); }
 };
 
-template <int MS, bool VEC16, bool A_LDS>
+template <int MS, bool VEC16, bool A_LDS, bool PRE>
 __global__ __launch_bounds__(256)
 void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B,
                   int32_t *__restrict__ C, int M, int N, int K_true, int row_words, int lpr,
@@ -599,12 +599,6 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
     const chunk_t *Ag = reinterpret_cast<const chunk_t *>(A);
     const chunk_t *Bg = reinterpret_cast<const chunk_t *>(B);
 
-    if (A_LDS) {
-        for (int i = threadIdx.x; i < MS * nch; i += blockDim.x)
-            As[i] = (i / nch < M) ? Ag[i] : CK::zero();
-        __syncthreads();
-    }
-
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int waves_per_block = blockDim.x / kWave;
@@ -614,6 +608,24 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
     const int64_t groups = ((int64_t)N + rpw - 1) / rpw;
     // a block owns a contiguous run of rows, so that the blocks in flight sweep B as one front
     const int64_t g0 = ((int64_t)blockIdx.x * waves_per_block + wave) * groups_per_wave;
+
+    // PRE (one row group per wave: a product whose time is a chain of latencies): the weights
+    // are the long pole, so the first loads of the wave's row go out before A is staged (rows
+    // beyond N read row N - 1; their results are not stored)
+    chunk_t pre0 = CK::zero(), pre1 = CK::zero();
+    if (PRE) {
+        const int64_t row = min(g0 * rpw + sub, (int64_t)N - 1);
+        const chunk_t *brow = Bg + row * nch;
+        if (cl < nch)
+            pre0 = brow[cl];
+        if (cl + lpr < nch)
+            pre1 = brow[cl + lpr];
+    }
+    if (A_LDS) {
+        for (int i = threadIdx.x; i < MS * nch; i += blockDim.x)
+            As[i] = (i / nch < M) ? Ag[i] : CK::zero();
+        __syncthreads();
+    }
 
     for (int64_t g = g0; g < g0 + groups_per_wave && g < groups; ++g) {
         const int64_t row = g * rpw + sub;
@@ -626,8 +638,9 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
         int c = cl;
         // two chunks per trip keep more loads in flight
         for (; c + lpr < nch; c += 2 * lpr) {
-            const chunk_t b0 = valid ? brow[c] : CK::zero();
-            const chunk_t b1 = valid ? brow[c + lpr] : CK::zero();
+            const bool first = PRE && g == g0 && c == cl;
+            const chunk_t b0 = first ? pre0 : (valid ? brow[c] : CK::zero());
+            const chunk_t b1 = first ? pre1 : (valid ? brow[c + lpr] : CK::zero());
 #pragma unroll
             for (int m = 0; m < MS; ++m) {
                 const chunk_t a0 = A_LDS ? As[m * nch + c] : (m < M ? Ag[m * nch + c] : CK::zero());
@@ -637,7 +650,8 @@ void bgemv_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B
             }
         }
         if (c < nch) {
-            const chunk_t b0 = valid ? brow[c] : CK::zero();
+            const bool first = PRE && g == g0 && c == cl;
+            const chunk_t b0 = first ? pre0 : (valid ? brow[c] : CK::zero());
 #pragma unroll
             for (int m = 0; m < MS; ++m) {
                 const chunk_t a0 = A_LDS ? As[m * nch + c] : (m < M ? Ag[m * nch + c] : CK::zero());
@@ -681,11 +695,14 @@ static int launch_gemv2(const uint64_t *A, const uint64_t *B, int32_t *C, int64_
     gpw = gpw < 1 ? 1 : (gpw > 4 ? 4 : gpw);
     const unsigned grid = grid_for(groups, 4 /* waves per block */ * gpw);
     const size_t lds = (size_t)MS * row_words * 8;
-    if (lds <= kGemvLdsBytes)
-        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, true>), dim3(grid), dim3(256), lds, stream, A, B, C,
+    if (lds <= kGemvLdsBytes && gpw == 1)
+        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, true, true>), dim3(grid), dim3(256), lds, stream, A, B, C,
+                           (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw, c_stride_m, c_stride_row);
+    else if (lds <= kGemvLdsBytes)
+        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, true, false>), dim3(grid), dim3(256), lds, stream, A, B, C,
                            (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw, c_stride_m, c_stride_row);
     else
-        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, false>), dim3(grid), dim3(256), 0, stream, A, B, C,
+        hipLaunchKernelGGL((bgemv_kernel<MS, VEC16, false, false>), dim3(grid), dim3(256), 0, stream, A, B, C,
                            (int)M, (int)N, (int)K_true, (int)row_words, lpr, gpw, c_stride_m, c_stride_row);
     return launch_status();
 }
