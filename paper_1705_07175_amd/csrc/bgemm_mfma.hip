@@ -300,8 +300,11 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
                             const int row = wm + f * 32 + 8 * q + 4 * half + t;
 #pragma unroll
                             for (int w = 0; w < NW; ++w) {
-                                const uint32_t lo = (uint32_t)(mask[t][2 * w] >> (32 * half));
-                                const uint32_t hi = (uint32_t)(mask[t][2 * w + 1] >> (32 * half));
+                                // the halves of a mask are scalars: pick one per lane with a
+                                // select (a per-lane 64-bit shift of the mask costs several times that)
+                                const uint64_t ml = mask[t][2 * w], mh = mask[t][2 * w + 1];
+                                const uint32_t lo = half ? (uint32_t)(ml >> 32) : (uint32_t)ml;
+                                const uint32_t hi = half ? (uint32_t)(mh >> 32) : (uint32_t)mh;
                                 wt[row * WPT + (wn >> 6) + w] = ((uint64_t)hi << 32) | lo;
                             }
                         }
