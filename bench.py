@@ -419,6 +419,10 @@ def _networks(torch, esp, nets, synth, dev, only=None):
             net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev, engine=esp.ENGINE_AUTO)
             res["bmlp"][str(batch) + "_auto_engine"] = time_net(net, x, batch, 50)
             del net
+            # ... and the bit-plane first layer as well (one call, planes combined in its epilogue)
+            net = nets.BinaryMLP(layers, batch, synth.BN_EPS, dev, first_layer="bitplane", engine=esp.ENGINE_AUTO)
+            res["bmlp"][str(batch) + "_bitplane_first_layer_auto_engine"] = time_net(net, x8, batch, 50)
+            del net
     layers = synth.cnn_params()
     for batch in (1, 256):
         if only and only != ("bcnn", batch):

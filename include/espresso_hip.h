@@ -326,6 +326,23 @@ int esp_bitplane_combine(const int32_t *d, const int32_t *wsum, int32_t *y, int6
                          int64_t inner, int64_t N, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
+/* Dense layer on 8-bit inputs in one call (Sec. 4.3, Eq. 3), on the matrix    */
+/* cores: the binary product of the 8 bit-planes of every input row with W and */
+/* their weighted combination, which happens in the product's epilogue (the    */
+/* eight partial results never reach memory).                                  */
+/*   planes uint64 [rows][8][ceil(K/64)]  (esp_bitplane_pack_u8 with inner = 1) */
+/*   W      uint64 [N][ceil(K/64)], wsum int32 [N] (esp_row_sums)              */
+/*   y      int32 [rows][N] = sum_k x[r][k] * w[n][k]           (optional)     */
+/*   bits   uint64 [rows][ceil(N/64)], bit n = (y >= thr[n]) XOR flipbit(n),   */
+/*          thr / flip as from esp_bn_fold                      (optional)     */
+/* At least one of y and bits.  Identical to esp_bgemm on the planes, then     */
+/* esp_bitplane_combine, then esp_bn_sign_pack.  K < 2^21.                     */
+/* ------------------------------------------------------------------------- */
+int esp_bitplane_dense(const uint64_t *planes, const uint64_t *W, const int32_t *wsum,
+                       const int32_t *thr, const uint64_t *flip, uint64_t *bits, int32_t *y,
+                       int64_t rows, int64_t N, int64_t K, esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
 /* Measurement aid: the in-register ceiling of the inner loop of Eq. 2 (Sec.  */
 /* 4.2, with XOR for XNOR).  Launches `blocks` blocks of 256 lanes; every lane */
 /* runs `iters` rounds of an 8 x 8 register block of v_xor_b32 + accumulating  */

@@ -30,7 +30,7 @@ EXPORTS = (
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
     "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2", "esp_dense_f32_bn_sign_pack",
-    "esp_xor_popcount_probe",
+    "esp_xor_popcount_probe", "esp_bitplane_dense",
 )
 
 _lib = None
@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
         l.esp_dense_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_xor_popcount_probe.argtypes = [vp, i32, i32, vp, vp]
+        l.esp_bitplane_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_version.argtypes = []
         for name in EXPORTS:
             # without a prototype ctypes would pass pointers as 32-bit ints: refuse to load
@@ -474,6 +475,28 @@ def bitplane_combine(d: torch.Tensor, wsum: torch.Tensor, out: torch.Tensor | No
     _check(lib().esp_bitplane_combine(pd, _dev(wsum, torch.int32, "wsum"), _dev(out, torch.int32, "out"),
                                       outer, inner, N, _stream()), "esp_bitplane_combine")
     return out
+
+
+def bitplane_dense(planes: torch.Tensor, w: torch.Tensor, wsum: torch.Tensor, k: int,
+                   thr: torch.Tensor | None = None, flip: torch.Tensor | None = None,
+                   bits: torch.Tensor | None = None, y: torch.Tensor | None = None, want_y: bool = False):
+    """``esp_bitplane_dense``: planes [rows][8][Kw] x W [N][Kw] -> (bits [rows][Nw] if thr is given, y
+    int32 [rows][N] if asked for)."""
+    pp, pw = _dev(planes, PACKED, "planes"), _dev(w, PACKED, "w")
+    rows, N = planes.shape[0], w.shape[0]
+    if planes.shape[1] != 8 or wsum.numel() != N:
+        raise ValueError("planes must be [rows][8][Kw], wsum one value per row of w")
+    if thr is not None:
+        bits = _out(bits, (rows, words(N)), PACKED, planes.device)
+    if want_y or y is not None:
+        y = _out(y, (rows, N), torch.int32, planes.device)
+    _check(lib().esp_bitplane_dense(pp, pw, _dev(wsum, torch.int32, "wsum"),
+                                    _dev(thr, torch.int32, "thr") if thr is not None else None,
+                                    _dev(flip, PACKED, "flip") if thr is not None else None,
+                                    _dev(bits, PACKED, "bits") if thr is not None else None,
+                                    _dev(y, torch.int32, "y") if y is not None else None,
+                                    rows, N, int(k), _stream()), "esp_bitplane_dense")
+    return bits, y
 
 
 def xor_popcount_probe(sink: torch.Tensor, blocks: int, iters: int) -> int:

@@ -91,6 +91,9 @@ struct MfmaOut {
     int pool_log2w;         // 0: no pooling; else bits is [M/4][Nw] behind a fused 2x2 max-pool
                             // and this is log2 of the convolution's output width W2
     int vec_store;          // C is 16-byte aligned and N a multiple of 4: 16-byte stores
+    const int32_t *wsum;    // bit-plane mode (Eq. 3): rows 8j .. 8j+7 of A are the planes of input
+                            // row j; C (optional) is then y [M/8][N] = (sum_i 2^i dot_i + 255 wsum) / 2
+                            // and bits (optional) [M/8][Nw] its thresholded sign; else null
 };
 
 template <class ASrc, bool VEC16B, bool BITS, int WM, int WN, int FM, int FN>
@@ -331,6 +334,59 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             __syncthreads();
             pool_tile_store<BM, WPT, NT>(wt, o.bits, m0, n0, M, o.Nw, o.pool_log2w, tid);
         }
+    } else if (o.wsum) {
+        // Bit-plane mode: the 8 planes of an input row sit in one group of 8 tile rows, planes
+        // 0-3 in lanes 0-31 and planes 4-7 in lanes 32-63 of the same registers; each half adds
+        // its four weighted dots and the halves meet through a lane exchange.
+        const int64_t images = M >> 3;
+        int ws[FN], lm[FN];
+#pragma unroll
+        for (int g = 0; g < FN; ++g) {
+            const int col = n0 + wn + g * 32 + lr;
+            ws[g] = col < N ? o.wsum[col] : 0;
+            lm[g] = (o.bits && col < N) ? o.thr[col] : 0x7fffffff;   // beyond N: bit 0
+        }
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rl = wm + f * 32 + 8 * q;
+                const int64_t img = (int64_t)(m0 + rl) >> 3;
+                const int4 pa4 = *reinterpret_cast<const int4 *>(&pa_s[rl + 4 * half]);
+                const int pav[4] = {pa4.x, pa4.y, pa4.z, pa4.w};
+                int yv[FN];
+#pragma unroll
+                for (int g = 0; g < FN; ++g) {
+                    int part = 0;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        part += (4 * (int)acc[f][g][4 * q + t] + kb[g] - 2 * pav[t]) << (4 * half + t);
+                    part += __shfl_xor(part, 32, kWave);
+                    yv[g] = (part + 255 * ws[g]) / 2;          // the sum is even
+                }
+                if (o.C && half == 0 && img < images) {
+#pragma unroll
+                    for (int g = 0; g < FN; ++g) {
+                        const int col = n0 + wn + g * 32 + lr;
+                        if (col < N)
+                            o.C[img * N + col] = yv[g];
+                    }
+                }
+                if (o.bits) {
+                    uint32_t m32[FN];
+#pragma unroll
+                    for (int g = 0; g < FN; ++g)
+                        m32[g] = (uint32_t)__ballot(yv[g] >= lm[g]);     // both halves hold the same values
+                    if (lane == 0 && img < images) {
+#pragma unroll
+                        for (int w = 0; w < FN / 2; ++w) {
+                            const int wi = ((n0 + wn) >> 6) + w;
+                            if (wi < o.Nw)
+                                o.bits[img * o.Nw + wi] = (((uint64_t)m32[2 * w + 1] << 32) | m32[2 * w]) ^ o.flip[wi];
+                        }
+                    }
+                }
+            }
     } else if (o.vec_store) {
         // int32 out, 16-byte stores: a 32 x 32 block leaves the accumulators as lane -> column,
         // register -> row; it is turned through a 4 KB LDS patch of the wave's own (the A slabs
@@ -400,7 +456,7 @@ static int launch_mfma_shape(const ASrc &asrc, const uint32_t *b, const MfmaOut 
         return ESP_ESHAPE;
     const int per_xcd = (int)ceil_div(total, kXcd);
     const dim3 grid((unsigned)(per_xcd * kXcd));
-    if (o.bits)
+    if (o.bits && !o.wsum)
         hipLaunchKernelGGL((bgemm_mfma_kernel<ASrc, VEC16B, true, S::WM, S::WN, S::FM, S::FN>), grid, dim3(256), 0,
                            stream, asrc, b, o, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
                            per_xcd);
@@ -431,10 +487,31 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
         return ESP_OK;
     if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29) || K_true >= kMaxMfmaK)
         return ESP_ESHAPE;
-    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64), 0, (N % 4 == 0) && aligned(C, 16)};
+    const MfmaOut o{C, bits, thr, flip, (int)ceil_div(N, 64), 0, (N % 4 == 0) && aligned(C, 16), nullptr};
     const bool vec16 = (row_words % 2 == 0) && aligned(A, 16) && aligned(B, 16);
     const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(B);
+    const int row_dw = (int)(row_words * 2);
+    if (vec16)
+        return launch_mfma<MatrixA<true>, true>(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw,
+                                                stream);
+    return launch_mfma<MatrixA<false>, false>(MatrixA<false>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw,
+                                              stream);
+}
+
+// Dense layer on 8-bit inputs given as bit-planes [rows][8][row_words] (Eq. 3): y and / or the
+// thresholded sign bits per input row, the combination done in the product's epilogue.
+int bitplane_dense_mfma_launch(const uint64_t *planes, const uint64_t *W, const int32_t *wsum, int32_t *y,
+                               const int32_t *thr, const uint64_t *flip, uint64_t *bits, int64_t rows, int64_t N,
+                               int64_t K_true, int64_t row_words, hipStream_t stream)
+{
+    const int64_t M = rows * 8;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || row_words >= (1ll << 29) || K_true >= (1 << 21))
+        return ESP_ESHAPE;        // 2 * 255 * K must stay inside int32
+    const MfmaOut o{y, bits, thr, flip, (int)ceil_div(N, 64), 0, 0, wsum};
+    const bool vec16 = (row_words % 2 == 0) && aligned(planes, 16) && aligned(W, 16);
+    const uint32_t *a = reinterpret_cast<const uint32_t *>(planes);
+    const uint32_t *b = reinterpret_cast<const uint32_t *>(W);
     const int row_dw = (int)(row_words * 2);
     if (vec16)
         return launch_mfma<MatrixA<true>, true>(MatrixA<true>{a, (int)M, row_dw}, b, o, M, N, K_true, row_dw,
@@ -452,7 +529,7 @@ int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, 
     if (M >= (1ll << 31) || K_true >= kMaxMfmaK || (int64_t)B * H * W * (C / 32) >= (1ll << 40))
         return ESP_ESHAPE;
     const ConvA a = make_conv_a(in, B, H, W, C, kh, kw, stride, pad, H2, W2);
-    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64), pool_log2w, (L2 % 4 == 0) && aligned(C_out, 16)};
+    const MfmaOut o{C_out, bits_out, thr, flip, (int)ceil_div(L2, 64), pool_log2w, (L2 % 4 == 0) && aligned(C_out, 16), nullptr};
     return launch_mfma<ConvA, true>(a, reinterpret_cast<const uint32_t *>(filt), o, M, L2, K_true, a.row_dw,
                                     stream);
 }

@@ -132,3 +132,23 @@ extern "C" int esp_bitplane_combine(const int32_t *d, const int32_t *wsum, int32
                        d, wsum, y, outer, inner, (int)N);
     return launch_status();
 }
+
+extern "C" int esp_bitplane_dense(const uint64_t *planes, const uint64_t *W, const int32_t *wsum,
+                                  const int32_t *thr, const uint64_t *flip, uint64_t *bits, int32_t *y,
+                                  int64_t rows, int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (rows < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (K >= (1 << 21))
+        return ESP_ESHAPE;
+    if (rows == 0)
+        return ESP_OK;
+    if (!planes || !W || !wsum || (!bits && !y) || (bits && (!thr || !flip)))
+        return ESP_EINVAL;
+    if (!aligned(planes, 8) || !aligned(W, 8) || !aligned(wsum, 4) || !aligned(thr, 4) || !aligned(flip, 8) ||
+        !aligned(bits, 8) || !aligned(y, 4))
+        return ESP_EALIGN;
+    return bitplane_dense_mfma_launch(planes, W, wsum, y, thr, flip, bits, rows, N, K, ceil_div(K, 64),
+                                      as_stream(stream));
+}

@@ -97,6 +97,12 @@ int bgemm_mfma_launch(const uint64_t *A, const uint64_t *B, int32_t *C, const in
                       const uint64_t *flip, uint64_t *bits, int64_t M, int64_t N, int64_t K_true,
                       int64_t row_words, hipStream_t stream);
 
+// Dense layer on 8-bit inputs given as bit-planes [rows][8][row_words] (Eq. 3), on the matrix
+// cores, the planes combined in the epilogue: y int32 [rows][N] and / or bits (+ thr, flip).
+int bitplane_dense_mfma_launch(const uint64_t *planes, const uint64_t *W, const int32_t *wsum, int32_t *y,
+                               const int32_t *thr, const uint64_t *flip, uint64_t *bits, int64_t rows, int64_t N,
+                               int64_t K_true, int64_t row_words, hipStream_t stream);
+
 // Convolution without a lowered matrix: the tile loader gathers the sliding volumes from
 // the packed NHWC input.  Usable when C is a multiple of 128 and the buffers are 16-byte
 // aligned.  Exactly one of C_out (int32 [B][H2][W2][L2]) and bits_out (+ thr, flip) is set.

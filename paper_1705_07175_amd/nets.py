@@ -57,6 +57,10 @@ class BinaryMLP:
         self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
         self.w1 = _dev_f32(layers[0]["w"], device)
         bitplane = first_layer == "bitplane"
+        # the bit-plane layer as one matrix-core call (planes combined in the product's epilogue)
+        # when the engine allows the matrix cores and the batch gives them enough tiles
+        self.bitplane_fused = bitplane and fused and (
+            engine == esp.ENGINE_MFMA or (engine == esp.ENGINE_AUTO and batch >= 64))
         self.bn = [_FoldedBN(l["bn"], eps, device, integer=(i > 0 or bitplane)) if l["bn"] is not None else None
                    for i, l in enumerate(layers)]
         self.wp = [None] + [_pack_weights(l["w"], device) for l in layers[1:]]
@@ -74,7 +78,13 @@ class BinaryMLP:
         torch.cuda.synchronize()
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
-        if self.first_layer == "bitplane":
+        if self.first_layer == "bitplane" and self.bitplane_fused:
+            # planes, then ONE call: product of the planes, their combination and the threshold
+            esp.bitplane_pack_u8(x, out=self.planes)
+            esp.bitplane_dense(self.planes, self.wp[0], self.wsum0, self.sizes[0], thr=self.bn[0].thr,
+                               flip=self.bn[0].flip, bits=self.act[0],
+                               y=self.pre[0] if self.keep_first_pre else None)
+        elif self.first_layer == "bitplane":
             esp.bitplane_pack_u8(x, out=self.planes)
             esp.bgemm(self.planes.view(self.batch * 8, -1), self.wp[0], self.sizes[0],
                       out=self.plane_dots.view(self.batch * 8, -1))

@@ -94,6 +94,23 @@ def test_mlp_forward_bitplane_first_layer(batch):
     assert np.array_equal(scores, ref[3]["pre"])
 
 
+@pytest.mark.parametrize("batch,engine", [(3, 1), (70, 2), (1024, 2)])
+def test_mlp_forward_bitplane_first_layer_fused(batch, engine):
+    # the same with the first layer as one matrix-core call (planes combined in the epilogue) and the
+    # other layers fused as well: bits and scores identical to the oracle (sampled rows at batch 1024)
+    layers = synth.mlp_params()
+    x = np.minimum(255, np.floor(synth.mlp_input(batch) * 256.0)).astype(np.uint8)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, first_layer="bitplane", engine=engine, keep_first_pre=True)
+    assert net.bitplane_fused
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    rows = np.arange(batch) if batch <= 70 else np.array([0, 1, 255, 256, 777, 1023])
+    ref = onets.mlp_forward(x[rows], layers, EPS)
+    assert np.array_equal(net.pre[0].cpu().numpy()[rows], ref[0]["pre"])
+    for i in (0, 1, 2):
+        assert np.array_equal(esp.packed_to_numpy(net.act[i])[rows], oracle.pack_bits(ref[i]["act"]))
+    assert np.array_equal(scores[rows], ref[3]["pre"])
+
+
 @pytest.mark.parametrize("engine", [0, 1])
 def test_mlp_batch1024_sampled_rows(engine):
     # full-size batch on the GPU; the oracle recomputes a sample of the (independent) rows

@@ -505,6 +505,34 @@ def test_bitplane_dense(M, N, K):
     assert np.array_equal(y.cpu().numpy(), oracle.dense_u8(x, w))
 
 
+# the same layer as ONE call on the matrix cores (planes combined in the product's epilogue): y and
+# the thresholded sign bits against the oracle's exact integer layer; row counts and widths that leave
+# partial tiles, K with an odd number of words (8-byte loads), both block shapes
+@pytest.mark.parametrize("M,N,K", [(1, 10, 64), (3, 70, 200), (64, 4096, 784), (33, 130, 1000), (300, 257, 832),
+                                   (1024, 4096, 784), (5, 64, 4096)])
+def test_bitplane_dense_fused(M, N, K):
+    rng = np.random.default_rng(M + 3 * N + 5 * K)
+    x = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    x[0, : min(K, 4)] = [0, 255, 1, 128][: min(K, 4)]
+    w = _pm1(rng, (N, K))
+    wp = _packed_dev(w)
+    planes = esp.bitplane_pack_u8(torch.from_numpy(x).to(DEV))
+    wsum = esp.row_sums(wp, K)
+    want = oracle.dense_u8(x, w)
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * 40 * np.sqrt(K)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    thr_d, flip_d = torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV)
+    want_bits = oracle.pack_bits(oracle.bn_sign(want, bnp, synth.BN_EPS))
+    bits, y = esp.bitplane_dense(planes, wp, wsum, K, thr=thr_d, flip=flip_d, want_y=True)
+    assert np.array_equal(y.cpu().numpy(), want)
+    assert np.array_equal(esp.packed_to_numpy(bits), want_bits)
+    bits_only, none = esp.bitplane_dense(planes, wp, wsum, K, thr=thr_d, flip=flip_d)
+    assert none is None and torch.equal(bits_only, bits)
+    none, y_only = esp.bitplane_dense(planes, wp, wsum, K, want_y=True)
+    assert none is None and torch.equal(y_only, y)
+
+
 @pytest.mark.parametrize("B,H,W,C,L2", [(2, 32, 32, 3, 128), (3, 6, 5, 3, 20), (1, 8, 8, 70, 9)])
 def test_bitplane_conv(B, H, W, C, L2):
     rng = np.random.default_rng(B + H + C + L2)
