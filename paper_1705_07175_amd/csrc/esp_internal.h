@@ -23,14 +23,16 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 inline bool engine_valid(int e) { return e == ESP_ENGINE_XOR_POPCOUNT || e == ESP_ENGINE_MFMA || e == ESP_ENGINE_AUTO; }
 
-// ESP_ENGINE_AUTO -> a concrete engine for an M x N product of length K: the matrix-core
-// kernel works on 256 x 128 tiles and pays off once those cover at least half of the 256 CUs.
+// ESP_ENGINE_AUTO -> a concrete engine for an M x N product of length K.  Measured break-even
+// of the two engines on the networks' layers: the matrix cores win from 32 of their 256 x 128
+// tiles on, provided a tile's 256 rows exist (a dense layer at batch 128 is better off on the
+// vector ALUs, at batch 256 on the matrix cores).
 inline int resolve_engine(int e, int64_t M, int64_t N, int64_t K)
 {
     if (e != ESP_ENGINE_AUTO)
         return e;
     const int64_t tiles = ceil_div(M, 256) * ceil_div(N, 128);
-    return (tiles >= 64 && K < (1ll << 24)) ? ESP_ENGINE_MFMA : ESP_ENGINE_XOR_POPCOUNT;
+    return (tiles >= 32 && M >= 256 && K < (1ll << 24)) ? ESP_ENGINE_MFMA : ESP_ENGINE_XOR_POPCOUNT;
 }
 
 // Division of a 32-bit unsigned value by a run-time constant, done as a
