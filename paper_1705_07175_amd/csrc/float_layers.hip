@@ -23,6 +23,188 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // (sgn[n] * y >= thr[n])): the 64-lane mask of a comparison holds 32 column bits of two rows,
 // lanes 0 and 32 drop them into an LDS table and 64 threads store one packed word (BN = 64)
 // or one 32-bit half of a word (BN = 32) per row; Y is then written only if not null.
+// ---------------------------------------------------------------------------------
+// Real-valued dense layer with +-1 weights on the bf16 matrix cores.  A float is the exact sum
+// of three bf16 values (8 + 8 + 8 significant bits: x = hi + mid + lo, each obtained by
+// truncation and an exact subtraction) and a +-1 weight IS a bf16 value, so
+//   sum_k x_k w_k = sum_k hi_k w_k + sum_k mid_k w_k + sum_k lo_k w_k
+// with every product exact and fp32 accumulation: three bf16 MFMAs (2.5 PFLOP/s) replace one
+// fp32 MFMA (157 TFLOP/s).  Weights that are not representable in bf16 would be truncated to 8
+// significant bits; the layers of a binary network (Sec. 4.3: real-valued input, binary
+// weights) never are.
+//   block tile BM x 128, 2 x 2 waves of (BM/2) x 64, K in slabs of 64 (four 32x32x16 steps);
+//   the slab is converted on its way from registers to LDS, where it sits row-major in bf16
+//   with a row pitch of 144 bytes (16-byte operand reads without bank conflicts).
+// ---------------------------------------------------------------------------------
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+
+// the three bf16 terms of four floats, as packed pairs (k, k+1), (k+2, k+3)
+__device__ __forceinline__ void split3(const float4 v, uint2 &hi, uint2 &mid, uint2 &lo)
+{
+    const float x[4] = {v.x, v.y, v.z, v.w};
+    uint32_t h[4], m[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[i] = __float_as_uint(x[i]) & 0xffff0000u;
+        const float r1 = x[i] - __uint_as_float(h[i]);
+        m[i] = __float_as_uint(r1) & 0xffff0000u;
+        l[i] = __float_as_uint(r1 - __uint_as_float(m[i]));    // at most 8 significant bits are left
+    }
+    hi = make_uint2(pack_hi16(h[0], h[1]), pack_hi16(h[2], h[3]));
+    mid = make_uint2(pack_hi16(m[0], m[1]), pack_hi16(m[2], m[3]));
+    lo = make_uint2(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]));
+}
+
+template <int BM, bool VEC4, bool FUSE>
+__global__ __launch_bounds__(256)
+void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ Wt, float *__restrict__ Y,
+                         const float *__restrict__ thr, const float *__restrict__ sgn,
+                         uint64_t *__restrict__ bits, int M, int N, int K)
+{
+    constexpr int BN = 128, BK = 64, PITCH = 72;          // bf16 elements per LDS row (144 bytes)
+    constexpr int FM = BM / 64;                           // 32-row blocks per wave
+    constexpr int XQ = BM * BK / 4 / 256, WQ = BN * BK / 4 / 256;
+    __shared__ __align__(16) uint16_t Xs[3][BM][PITCH];
+    __shared__ __align__(16) uint16_t Ws[BN][PITCH];
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    // unit u = tid + i * 256 -> row u / 16, k offset 4 * (u % 16): 16 lanes read 256 contiguous
+    // bytes; rows beyond the matrix read the last row (their results are not stored), the K tail
+    // reads 0
+    float4 xr[XQ], wr[WQ];
+    auto fetch = [&](const float *base, int row, int rows, int k0, int u) {
+        const int r = min(row + u / 16, rows - 1), k = k0 + 4 * (u % 16);
+        const float *p = base + (int64_t)r * K;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (VEC4) {
+            if (k < K)
+                v = *reinterpret_cast<const float4 *>(p + k);   // K % 4 == 0: whole or nothing
+        } else {
+            if (k + 0 < K) v.x = p[k + 0];
+            if (k + 1 < K) v.y = p[k + 1];
+            if (k + 2 < K) v.z = p[k + 2];
+            if (k + 3 < K) v.w = p[k + 3];
+        }
+        return v;
+    };
+    auto prefetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < XQ; ++i)
+            xr[i] = fetch(X, m0, M, k0, tid + i * 256);
+#pragma unroll
+        for (int i = 0; i < WQ; ++i)
+            wr[i] = fetch(Wt, n0, N, k0, tid + i * 256);
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < XQ; ++i) {
+            const int u = tid + i * 256, r = u / 16, k = 4 * (u % 16);
+            uint2 hi, mid, lo;
+            split3(xr[i], hi, mid, lo);
+            *reinterpret_cast<uint2 *>(&Xs[0][r][k]) = hi;
+            *reinterpret_cast<uint2 *>(&Xs[1][r][k]) = mid;
+            *reinterpret_cast<uint2 *>(&Xs[2][r][k]) = lo;
+        }
+#pragma unroll
+        for (int i = 0; i < WQ; ++i) {
+            const int u = tid + i * 256, r = u / 16, k = 4 * (u % 16);
+            const float4 w = wr[i];
+            *reinterpret_cast<uint2 *>(&Ws[r][k]) =
+                make_uint2(pack_hi16(__float_as_uint(w.x), __float_as_uint(w.y)),
+                           pack_hi16(__float_as_uint(w.z), __float_as_uint(w.w)));
+        }
+    };
+
+    const int lane = tid % kWave, wave = tid / kWave;
+    const int lr = lane % 32, half = lane / 32;
+    const int wm = (wave % 2) * (BM / 2);    // wave's row offset
+    const int wn = (wave / 2) * 64;          // wave's column offset: one 64-column word
+    float th[2], sg[2];                      // FUSE: threshold and sign of the lane's columns
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int n = n0 + wn + g * 32 + lr;
+        th[g] = (FUSE && n < N) ? thr[n] : 0.0f;
+        sg[g] = (FUSE && n < N) ? sgn[n] : 1.0f;
+    }
+    v16f acc[FM][2];
+#pragma unroll
+    for (int f = 0; f < FM; ++f)
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[f][g][r] = 0.0f;
+    prefetch(0);
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        commit();
+        __syncthreads();
+        if (k0 + BK < K)
+            prefetch(k0 + BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int ko = ks * 16 + 8 * half;
+            v8bf b[2];
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+                b[g] = *reinterpret_cast<const v8bf *>(&Ws[wn + g * 32 + lr][ko]);
+#pragma unroll
+            for (int f = 0; f < FM; ++f)
+#pragma unroll
+                for (int t = 2; t >= 0; --t) {     // smallest term first
+                    const v8bf a = *reinterpret_cast<const v8bf *>(&Xs[t][wm + f * 32 + lr][ko]);
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+                        acc[f][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[g], acc[f][g], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+
+    if (!FUSE || Y) {
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int n = n0 + wn + g * 32 + lr;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4;
+                    if (m < M && n < N)
+                        Y[(int64_t)m * N + n] = acc[f][g][r];
+                }
+            }
+    }
+    if (FUSE) {
+        // a wave's 64 columns are one output word per row: the comparison masks of its two column
+        // blocks give the word's halves; lanes 0 and 32 drop them into a table, then one thread
+        // per (row, word) stores
+        uint64_t *wt = reinterpret_cast<uint64_t *>(&Xs[0][0][0]);     // [BM][2], the slabs are done
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                uint64_t mask[2];
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+                    mask[g] = __ballot(n0 + wn + g * 32 + lr < N && sg[g] * acc[f][g][r] >= th[g]);
+                const uint32_t lo = half ? (uint32_t)(mask[0] >> 32) : (uint32_t)mask[0];
+                const uint32_t hi = half ? (uint32_t)(mask[1] >> 32) : (uint32_t)mask[1];
+                if (lr == 0)
+                    wt[(wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4) * 2 + wn / 64] = ((uint64_t)hi << 32) | lo;
+            }
+        __syncthreads();
+        const int Nw = (N + 63) / 64;
+        for (int t = tid; t < BM * 2; t += 256) {
+            const int row = m0 + t / 2, w = n0 / 64 + t % 2;
+            if (row < M && w < Nw)
+                bits[(int64_t)row * Nw + w] = wt[t];
+        }
+    }
+}
+
 template <int BN, bool VEC4, bool FUSE>
 __global__ __launch_bounds__(256)
 void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
@@ -568,6 +750,10 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
 
 namespace esp {
 
+// measured on the MLP's first layer (N = 4096, K = 784): fp32 kernel 18 / 26 / 38 / 67 us at
+// 128 / 256 / 512 / 1024 rows, bf16 kernel 21 / 21 / 21 / 27 us
+constexpr int64_t kDenseBf16MinRows = 256;
+
 // Tiled float dense layer; with bits != null the fused threshold epilogue (Y then optional).
 static int dense_mfma_launch(const float *X, const float *W, float *Y, const float *thr, const float *sgn,
                              uint64_t *bits, int64_t M, int64_t N, int64_t K, hipStream_t s)
@@ -576,6 +762,30 @@ static int dense_mfma_launch(const float *X, const float *W, float *Y, const flo
     if (gy > 65535)
         return ESP_ESHAPE;
     const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
+    if (M >= kDenseBf16MinRows) {
+        // the bf16 matrix cores (three exact terms per input)
+        const bool tall = ceil_div(M, 128) * ceil_div(N, 128) >= 512;
+        const dim3 grid((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, tall ? 128 : 64));
+#define ESP_DENSE_BF16(BMV, V)                                                                             \
+    do {                                                                                                   \
+        if (bits)                                                                                          \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
+                               bits, (int)M, (int)N, (int)K);                                              \
+        else                                                                                               \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
+                               bits, (int)M, (int)N, (int)K);                                              \
+    } while (0)
+        if (tall && vec4)
+            ESP_DENSE_BF16(128, true);
+        else if (tall)
+            ESP_DENSE_BF16(128, false);
+        else if (vec4)
+            ESP_DENSE_BF16(64, true);
+        else
+            ESP_DENSE_BF16(64, false);
+#undef ESP_DENSE_BF16
+        return launch_status();
+    }
     const bool narrow = gy * ceil_div(N, 64) < 256;   // few blocks: halve the tile width
     // the grid covers every word (or 32-bit half) of the packed rows, also columns beyond N
     const int64_t Nw = ceil_div(N, 64);

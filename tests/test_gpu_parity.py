@@ -570,7 +570,10 @@ def _assert_close_1e4(got, ref):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (3, 100, 50), (64, 4096, 784), (70, 130, 97), (4, 10, 784),
-                                   (1024, 4096, 784), (300, 1000, 130), (65, 33, 36), (5, 64, 31), (2000, 700, 100)])
+                                   (1024, 4096, 784), (300, 1000, 130), (65, 33, 36), (5, 64, 31), (2000, 700, 100),
+                                   # 256 rows and more: the three-term bf16 kernel; K not a multiple of 4 or of
+                                   # its 64-wide slabs, ragged M and N, 64- and 128-row tiles
+                                   (256, 128, 64), (257, 130, 97), (300, 70, 131), (4100, 2050, 70), (8200, 8100, 40)])
 def test_dense_f32(M, N, K):
     rng = np.random.default_rng(M + N + K)
     x = rng.random((M, K), dtype=np.float32)
@@ -598,7 +601,8 @@ def test_conv_f32(B, H, W, C, L2, k, stride, pad):
 
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (2, 100, 50), (3, 64, 31), (4, 130, 784), (1, 65, 4),
                                    (4, 1000, 1001), (5, 4096, 784), (70, 130, 97), (2, 16390, 64),
-                                   (64, 4096, 784), (1024, 4096, 784), (300, 70, 130), (65, 33, 36)])
+                                   (64, 4096, 784), (1024, 4096, 784), (300, 70, 130), (65, 33, 36),
+                                   (256, 128, 64), (257, 130, 97), (8200, 4000, 40), (300, 200, 131)])
 def test_dense_f32_bn_sign_pack(M, N, K):
     # M <= 4: the streaming kernel (16 or 64 neurons per block); beyond: the matrix-core kernel
     rng = np.random.default_rng(M + 10 * N + 100 * K)
