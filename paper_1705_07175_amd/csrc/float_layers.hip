@@ -1,9 +1,10 @@
-// Real-valued first layer in fp32 (the non-binary variant of a layer, Sec. 3 of
+// Real-valued first layer (the non-binary variant of a layer, Sec. 3 of
 // arXiv 1705.07175): the networks of Sec. 6.2 / 6.3 start from real-valued images, so
 // their first dense / convolutional layer multiplies floats by +-1 weights.  These are
-// supporting kernels: an LDS-tiled SGEMM on the fp32 matrix cores, a wave-per-output GEMV for
-// tiny batches, a direct convolution with the filters transposed in LDS for general shapes,
-// and the 3x3x3 first layer of the CIFAR-10 network, again on the fp32 matrix cores.
+// supporting kernels: LDS-tiled dense layers on the matrix cores (fp32 operands, or three exact
+// bf16 terms per input from 256 rows on), a wave-per-output GEMV for tiny batches, a direct
+// convolution with the filters transposed in LDS for general shapes, and the 3x3x3 first layer
+// of the CIFAR-10 network on the bf16 matrix cores (three exact terms per input as well).
 #include "esp_internal.h"
 
 namespace esp {
@@ -19,10 +20,6 @@ namespace esp {
 // Result layout of the MFMA: lane -> column lane % 32, register r -> row 8 (r/4) + 4 (lane/32) + r%4.
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// With FUSE the folded batch-norm threshold + sign is applied in the epilogue (bit n of row m =
-// (sgn[n] * y >= thr[n])): the 64-lane mask of a comparison holds 32 column bits of two rows,
-// lanes 0 and 32 drop them into an LDS table and 64 threads store one packed word (BN = 64)
-// or one 32-bit half of a word (BN = 32) per row; Y is then written only if not null.
 // ---------------------------------------------------------------------------------
 // Real-valued dense layer with +-1 weights on the bf16 matrix cores.  A float is the exact sum
 // of three bf16 values (8 + 8 + 8 significant bits: x = hi + mid + lo, each obtained by
@@ -205,6 +202,10 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
     }
 }
 
+// With FUSE the folded batch-norm threshold + sign is applied in the epilogue (bit n of row m =
+// (sgn[n] * y >= thr[n])): the 64-lane mask of a comparison holds 32 column bits of two rows,
+// lanes 0 and 32 drop them into an LDS table and 64 threads store one packed word (BN = 64)
+// or one 32-bit half of a word (BN = 32) per row; Y is then written only if not null.
 template <int BN, bool VEC4, bool FUSE>
 __global__ __launch_bounds__(256)
 void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
@@ -515,15 +516,17 @@ void conv_f32_kernel(const float *__restrict__ in, const float *__restrict__ fil
     }
 }
 
-// Fast path for the 3x3x3 first layer of the Sec. 6.3 network at stride 1, on the fp32 matrix
-// cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation, twice the rate of the
-// unpacked vector FMA).  The layer is the dense contraction
-//   out[pixel][l2] = sum_k window[pixel][k] * filt[l2][k],  k = (dy, dx, c) < 27 (padded to 28),
+// Fast path for the 3x3x3 first layer of the Sec. 6.3 network at stride 1, on the bf16 matrix
+// cores: every window value is split exactly into three bf16 terms (split3) and the +-1 filter
+// values are bf16 values, so three v_mfma_f32_32x32x16_bf16 per k-step give the fp32 sum of
+// exact products (a filter value that is not representable in bf16 would be cut to 8
+// significant bits).  The layer is the dense contraction
+//   out[pixel][l2] = sum_k window[pixel][k] * filt[l2][k],  k = (dy, dx, c) < 27 (padded to 32),
 // so a wave owns a strip of 32 consecutive output pixels of one output row (= the 32 rows of
 // the MFMA's A operand) and NB blocks of 32 output channels (the columns):
 //  * the wave copies the strip's input window (3 rows x 34 pixels x 3 channels, zeros outside
-//    the image) into its private LDS slice; lane (pixel p, k-half h) reads element
-//    (p, k = 2 s + h) of the lowered window for step s straight from there;
+//    the image) into its private LDS slice; lane (pixel p, k-half h) reads the elements
+//    (p, k = 16 s + 8 h + j), j = 0..7, of the lowered window for step s straight from there;
 //  * the weights of the wave's channels stay in registers as B operands for all its strips;
 //  * with FUSE the per-channel sign of the folded batch-norm is multiplied into the weights
 //    (exact), so the epilogue is one compare per accumulator whose 64-lane mask holds the
@@ -547,7 +550,7 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
                            int H, int W, int L2, int pad, int H2, int W2, int strips, int rows_strips,
                            int tasks)
 {
-    constexpr int T = 27, KS = 14;                 // taps * channels, k-steps of 2
+    constexpr int T = 27, KS = 2;                  // taps * channels, k-steps of 16 (k padded to 32)
     constexpr int PIX = 32, WROW = (PIX + 2) * 3;  // floats per window row
     constexpr int WIN = 3 * WROW;
     static_assert(NB == 1 || NB == 4, "one block per wave (32-bit output pieces) or whole words");
@@ -588,16 +591,19 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
         wdst[q] = i < WIN ? i : WIN + 1;           // WIN + 1: scratch slot
     }
 
-    // lowered-window element (pixel lr, k) sits at 93 * dy + 3 * lr + k, dy = k / 9
-    int off[KS];
+    // lowered-window element (pixel lr, k) sits at 93 * dy + 3 * lr + k, dy = k / 9; a lane's
+    // operand of k-step s holds k = 16 s + 8 half + j, j = 0..7 (k >= 27: the zero slot)
+    int off[KS][8];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        const int k = 2 * s + half;
-        off[s] = k < T ? 93 * (k / 9) + 3 * lr + k : WIN;
-    }
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = 16 * s + 8 * half + j;
+            off[s][j] = k < T ? 93 * (k / 9) + 3 * lr + k : WIN;
+        }
 
     const int Cw = (L2 + 63) / 64;
-    float bw[NB][KS];
+    v8bf bw[NB][KS];       // filter values x folded sign: +-1 (or 0), exact in bf16
     float th[NB], sg[NB];
     int cur_cg = -1;
     const int nwaves = gridDim.x * (blockDim.x / kWave);
@@ -646,19 +652,22 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
                     sg[nb] = 1.0f;
                     th[nb] = __builtin_inff();         // beyond L2: bit 0
                 }
-                float wv[KS];
-                if (cg == cg_staged) {                // wave-uniform
 #pragma unroll
-                    for (int s = 0; s < KS; ++s)
-                        wv[s] = filt_s[(nb * 32 + lr) * T + min(2 * s + half, T - 1)];
-                } else {
+                for (int s = 0; s < KS; ++s) {
+                    float wv[8];
+                    if (cg == cg_staged) {            // wave-uniform
 #pragma unroll
-                    for (int s = 0; s < KS; ++s)
-                        wv[s] = filt[(int64_t)l2c * T + min(2 * s + half, T - 1)];
+                        for (int j = 0; j < 8; ++j)
+                            wv[j] = filt_s[(nb * 32 + lr) * T + min(16 * s + 8 * half + j, T - 1)];
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            wv[j] = filt[(int64_t)l2c * T + min(16 * s + 8 * half + j, T - 1)];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        bw[nb][s][j] = (__bf16)keep_if(sg[nb] * wv[j], ok && 16 * s + 8 * half + j < T);
                 }
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    bw[nb][s] = keep_if(sg[nb] * wv[s], ok && 2 * s + half < T);
             }
         }
 
@@ -676,12 +685,26 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[nb][r] = 0.0f;
+        // every window value is the exact sum of three bf16 terms (see split3) and the weights
+        // are +-1, so three bf16 MFMAs per k-step give the fp32 sum of exact products
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const float a = win[off[s]];
+            uint2 hi[2], mid[2], lo[2];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bw[nb][s], acc[nb], 0, 0, 0);
+            for (int q = 0; q < 2; ++q)
+                split3(make_float4(win[off[s][4 * q]], win[off[s][4 * q + 1]], win[off[s][4 * q + 2]],
+                                   win[off[s][4 * q + 3]]), hi[q], mid[q], lo[q]);
+            const uint4 a3[3] = {make_uint4(lo[0].x, lo[0].y, lo[1].x, lo[1].y),
+                                 make_uint4(mid[0].x, mid[0].y, mid[1].x, mid[1].y),
+                                 make_uint4(hi[0].x, hi[0].y, hi[1].x, hi[1].y)};
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                v8bf a;
+                __builtin_memcpy(&a, &a3[t], 16);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw[nb][s], acc[nb], 0, 0, 0);
+            }
         }
 
         const int64_t pix0 = (int64_t)bm * W2 + n0;    // first output pixel of the strip
