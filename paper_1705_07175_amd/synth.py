@@ -39,7 +39,7 @@ CNN_LAYERS = (
 
 
 def rng_for(config: int, stream: int = 0) -> np.random.Generator:
-    """Generator for BASELINE config ``config``; ``stream`` picks an independent sub-stream."""
+    """Generator for workload configuration ``config`` (1-5); ``stream`` picks an independent sub-stream."""
     return np.random.default_rng([SEED0 + int(config), int(stream)])
 
 
