@@ -230,3 +230,13 @@ def test_bn_fold_f32_matches_oracle_around_every_threshold():
     want = oracle.sign(oracle.bn(x.astype(np.float64), g, b, m, v, synth.BN_EPS)) > 0
     got = (sgn[None, :] * x) >= thr[None, :]
     assert np.array_equal(got, want)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: the benchmark says so and exits before touching any device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode != 0 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
