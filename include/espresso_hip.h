@@ -252,11 +252,12 @@ int esp_bmaxpool(const uint64_t *in, uint64_t *out, int B, int H, int W, int C,
 /*   conv :  in float [B][H][W][C], filt float [L2][kh][kw][C] (+-1 values),  */
 /*           out float [B][H2][W2][L2], zero padding                          */
 /* The weights of these layers are the +-1 of a binary network held as floats */
-/* (Sec. 4.3: real-valued input, binary weights).  The dense layer from 256   */
-/* rows on and the 3x3x3 stride-1 convolution rely on that: they run on the   */
-/* bf16 matrix cores with every input split exactly into three bf16 terms and */
-/* the weights taken as bf16, which is exact for +-1 (any other weight would  */
-/* be cut to 8 significant bits); sums are accumulated in fp32 either way.    */
+/* (Sec. 4.3: real-valued input, binary weights).  esp_dense_f32 is plain     */
+/* fp32 for any weight values; the fused dense layer (more than 4 rows) and   */
+/* the 3x3x3 stride-1 convolution rely on the +-1: they run on the bf16       */
+/* matrix cores with every input split exactly into three bf16 terms and the  */
+/* weights taken as bf16, which is exact for +-1 (any other weight would be   */
+/* cut to 8 significant bits); sums are accumulated in fp32 either way.       */
 /* ------------------------------------------------------------------------- */
 int esp_dense_f32(const float *X, const float *W, float *Y,
                   int64_t M, int64_t N, int64_t K, esp_stream stream);

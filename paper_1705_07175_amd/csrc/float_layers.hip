@@ -54,13 +54,13 @@ __device__ __forceinline__ void split3(const float4 v, uint2 &hi, uint2 &mid, ui
     lo = make_uint2(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]));
 }
 
-template <int BM, bool VEC4, bool FUSE>
+template <int BM, int G, bool VEC4, bool FUSE>
 __global__ __launch_bounds__(256)
 void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ Wt, float *__restrict__ Y,
                          const float *__restrict__ thr, const float *__restrict__ sgn,
                          uint64_t *__restrict__ bits, int M, int N, int K)
 {
-    constexpr int BN = 128, BK = 64, PITCH = 72;          // bf16 elements per LDS row (144 bytes)
+    constexpr int BN = 64 * G, BK = 64, PITCH = 72;       // bf16 elements per LDS row (144 bytes)
     constexpr int FM = BM / 64;                           // 32-row blocks per wave
     constexpr int XQ = BM * BK / 4 / 256, WQ = BN * BK / 4 / 256;
     __shared__ __align__(16) uint16_t Xs[3][BM][PITCH];
@@ -118,19 +118,19 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
     const int lane = tid % kWave, wave = tid / kWave;
     const int lr = lane % 32, half = lane / 32;
     const int wm = (wave % 2) * (BM / 2);    // wave's row offset
-    const int wn = (wave / 2) * 64;          // wave's column offset: one 64-column word
-    float th[2], sg[2];                      // FUSE: threshold and sign of the lane's columns
+    const int wn = (wave / 2) * (32 * G);    // wave's column offset: a 64-column word (G = 2) or half of one
+    float th[G], sg[G];                      // FUSE: threshold and sign of the lane's columns
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
+    for (int g = 0; g < G; ++g) {
         const int n = n0 + wn + g * 32 + lr;
         th[g] = (FUSE && n < N) ? thr[n] : 0.0f;
         sg[g] = (FUSE && n < N) ? sgn[n] : 1.0f;
     }
-    v16f acc[FM][2];
+    v16f acc[FM][G];
 #pragma unroll
     for (int f = 0; f < FM; ++f)
 #pragma unroll
-        for (int g = 0; g < 2; ++g)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[f][g][r] = 0.0f;
@@ -143,9 +143,9 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int ko = ks * 16 + 8 * half;
-            v8bf b[2];
+            v8bf b[G];
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
+            for (int g = 0; g < G; ++g)
                 b[g] = *reinterpret_cast<const v8bf *>(&Ws[wn + g * 32 + lr][ko]);
 #pragma unroll
             for (int f = 0; f < FM; ++f)
@@ -153,7 +153,7 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
                 for (int t = 2; t >= 0; --t) {     // smallest term first
                     const v8bf a = *reinterpret_cast<const v8bf *>(&Xs[t][wm + f * 32 + lr][ko]);
 #pragma unroll
-                    for (int g = 0; g < 2; ++g)
+                    for (int g = 0; g < G; ++g)
                         acc[f][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[g], acc[f][g], 0, 0, 0);
                 }
         }
@@ -164,7 +164,7 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
 #pragma unroll
         for (int f = 0; f < FM; ++f)
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
+            for (int g = 0; g < G; ++g) {
                 const int n = n0 + wn + g * 32 + lr;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -175,42 +175,34 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
             }
     }
     if (FUSE) {
-        // a wave's 64 columns are one output word per row: the comparison masks of its two column
-        // blocks give the word's halves; lanes 0 and 32 drop them into a table, then one thread
-        // per (row, word) stores
-        uint64_t *wt = reinterpret_cast<uint64_t *>(&Xs[0][0][0]);     // [BM][2], the slabs are done
+        // the comparison masks of a wave's column blocks are 32-bit pieces of the output words:
+        // lanes 0 and 32 drop them into a table [row][piece], then one thread per (row, word) stores
+        uint32_t *wt = reinterpret_cast<uint32_t *>(&Xs[0][0][0]);     // [BM][2 G], the slabs are done
 #pragma unroll
         for (int f = 0; f < FM; ++f)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                uint64_t mask[2];
+            for (int r = 0; r < 16; ++r)
 #pragma unroll
-                for (int g = 0; g < 2; ++g)
-                    mask[g] = __ballot(n0 + wn + g * 32 + lr < N && sg[g] * acc[f][g][r] >= th[g]);
-                const uint32_t lo = half ? (uint32_t)(mask[0] >> 32) : (uint32_t)mask[0];
-                const uint32_t hi = half ? (uint32_t)(mask[1] >> 32) : (uint32_t)mask[1];
-                if (lr == 0)
-                    wt[(wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4) * 2 + wn / 64] = ((uint64_t)hi << 32) | lo;
-            }
+                for (int g = 0; g < G; ++g) {
+                    const uint64_t mask = __ballot(n0 + wn + g * 32 + lr < N && sg[g] * acc[f][g][r] >= th[g]);
+                    const uint32_t piece = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+                    if (lr == 0)
+                        wt[(wm + f * 32 + 8 * (r / 4) + 4 * half + r % 4) * (2 * G) + (wn / 32) + g] = piece;
+                }
         __syncthreads();
         const int Nw = (N + 63) / 64;
-        for (int t = tid; t < BM * 2; t += 256) {
-            const int row = m0 + t / 2, w = n0 / 64 + t % 2;
+        for (int t = tid; t < BM * G; t += 256) {
+            const int row = m0 + t / G, w = n0 / 64 + t % G;
             if (row < M && w < Nw)
-                bits[(int64_t)row * Nw + w] = wt[t];
+                bits[(int64_t)row * Nw + w] = reinterpret_cast<const uint64_t *>(wt)[t];
         }
     }
 }
 
-// With FUSE the folded batch-norm threshold + sign is applied in the epilogue (bit n of row m =
-// (sgn[n] * y >= thr[n])): the 64-lane mask of a comparison holds 32 column bits of two rows,
-// lanes 0 and 32 drop them into an LDS table and 64 threads store one packed word (BN = 64)
-// or one 32-bit half of a word (BN = 32) per row; Y is then written only if not null.
-template <int BN, bool VEC4, bool FUSE>
+template <int BN, bool VEC4>
 __global__ __launch_bounds__(256)
 void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict__ Wt,
-                           float *__restrict__ Y, const float *__restrict__ thr,
-                           const float *__restrict__ sgn, uint64_t *__restrict__ bits, int M, int N, int K)
+                           float *__restrict__ Y, int M, int N, int K)
 {
     constexpr int BM = 64, BK = 32;
     constexpr int XQ = BM * BK / 4 / 256;   // float4 units per thread and slab: 2
@@ -272,11 +264,6 @@ void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict_
     const int wm = (wave % 2) * 32;          // wave's row offset
     const int wn = WN == 2 ? (wave / 2) * 32 : 0;
     const int kpart = WN == 2 ? 0 : wave / 2;   // BN = 32: which of the alternate k-steps
-    float th = 0.0f, sg = 1.0f;              // FUSE: threshold and sign of the lane's column, fetched early
-    if (FUSE && n0 + wn + lr < N) {
-        th = thr[n0 + wn + lr];
-        sg = sgn[n0 + wn + lr];
-    }
     v16f acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -312,31 +299,12 @@ void dense_f32_mfma_kernel(const float *__restrict__ X, const float *__restrict_
         }
     }
     const int n = n0 + wn + lr;
-    if (owner && (!FUSE || Y)) {
+    if (owner) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + wm + 8 * (r / 4) + 4 * half + r % 4;
             if (m < M && n < N)
                 Y[(int64_t)m * N + n] = acc[r];
-        }
-    }
-    if (FUSE) {
-        __shared__ uint32_t wt[BM][WN];
-        if (owner) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint64_t mask = __ballot(n < N && sg * acc[r] >= th);
-                const uint32_t v = (uint32_t)(mask >> (32 * half));
-                if (lr == 0)
-                    wt[wm + 8 * (r / 4) + 4 * half + r % 4][wn / 32] = v;
-            }
-        }
-        __syncthreads();
-        if (tid < BM && m0 + tid < M) {
-            if (WN == 2)   // one word per row; grid.x = words per row
-                bits[(int64_t)(m0 + tid) * gridDim.x + blockIdx.x] = wt[tid][0] | ((uint64_t)wt[tid][WN - 1] << 32);
-            else           // one 32-bit half per row; grid.x = halves per row
-                reinterpret_cast<uint32_t *>(bits)[(int64_t)(m0 + tid) * gridDim.x + blockIdx.x] = wt[tid][0];
         }
     }
 }
@@ -773,11 +741,8 @@ void conv3x3x3_mfma_kernel(const float *__restrict__ in, const float *__restrict
 
 namespace esp {
 
-// measured on the MLP's first layer (N = 4096, K = 784): fp32 kernel 18 / 26 / 38 / 67 us at
-// 128 / 256 / 512 / 1024 rows, bf16 kernel 21 / 21 / 21 / 27 us
-constexpr int64_t kDenseBf16MinRows = 256;
-
-// Tiled float dense layer; with bits != null the fused threshold epilogue (Y then optional).
+// Tiled float dense layer: with bits != null the fused layer on the bf16 matrix cores (threshold
+// epilogue, Y optional), else the plain fp32 product.
 static int dense_mfma_launch(const float *X, const float *W, float *Y, const float *thr, const float *sgn,
                              uint64_t *bits, int64_t M, int64_t N, int64_t K, hipStream_t s)
 {
@@ -785,43 +750,44 @@ static int dense_mfma_launch(const float *X, const float *W, float *Y, const flo
     if (gy > 65535)
         return ESP_ESHAPE;
     const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
-    if (M >= kDenseBf16MinRows) {
-        // the bf16 matrix cores (three exact terms per input)
-        const bool tall = ceil_div(M, 128) * ceil_div(N, 128) >= 512;
-        const dim3 grid((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, tall ? 128 : 64));
-#define ESP_DENSE_BF16(BMV, V)                                                                             \
+    if (bits) {
+        // the fused layer of a binary network (+-1 weights): the bf16 matrix cores, three exact
+        // terms per input.  Measured on the MLP's first layer (N = 4096, K = 784) at 8 ... 256 /
+        // 512 / 1024 rows: 15.6 / 19.0 / 25.9 us (the fp32 kernel below: 17.4 ... 26 / 38 / 67 us)
+        // 128 x 128 tiles when there are many of them, else 64 x 128, else 64 x 64: the kernel is
+        // bound by the chain of its K slabs, so it wants several blocks per CU
+        const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
+        const int bm = t128 >= 1024 ? 128 : 64;
+        const int g = (bm == 128 || ceil_div(M, 64) * ceil_div(N, 128) >= 512) ? 2 : 1;
+        const dim3 grid((unsigned)ceil_div(N, 64 * g), (unsigned)ceil_div(M, bm));
+#define ESP_DENSE_BF16(BMV, GV, V)                                                                         \
     do {                                                                                                   \
         if (bits)                                                                                          \
-            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
-                               bits, (int)M, (int)N, (int)K);                                              \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, \
+                               sgn, bits, (int)M, (int)N, (int)K);                                         \
         else                                                                                               \
-            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
-                               bits, (int)M, (int)N, (int)K);                                              \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, \
+                               sgn, bits, (int)M, (int)N, (int)K);                                         \
     } while (0)
-        if (tall && vec4)
-            ESP_DENSE_BF16(128, true);
-        else if (tall)
-            ESP_DENSE_BF16(128, false);
+        if (bm == 128 && vec4)
+            ESP_DENSE_BF16(128, 2, true);
+        else if (bm == 128)
+            ESP_DENSE_BF16(128, 2, false);
+        else if (g == 2 && vec4)
+            ESP_DENSE_BF16(64, 2, true);
+        else if (g == 2)
+            ESP_DENSE_BF16(64, 2, false);
         else if (vec4)
-            ESP_DENSE_BF16(64, true);
+            ESP_DENSE_BF16(64, 1, true);
         else
-            ESP_DENSE_BF16(64, false);
+            ESP_DENSE_BF16(64, 1, false);
 #undef ESP_DENSE_BF16
         return launch_status();
     }
     const bool narrow = gy * ceil_div(N, 64) < 256;   // few blocks: halve the tile width
-    // the grid covers every word (or 32-bit half) of the packed rows, also columns beyond N
-    const int64_t Nw = ceil_div(N, 64);
-    const dim3 grid((unsigned)(narrow ? 2 * Nw : Nw), (unsigned)gy);
+    const dim3 grid((unsigned)ceil_div(N, narrow ? 32 : 64), (unsigned)gy);
 #define ESP_DENSE(BN, V)                                                                                   \
-    do {                                                                                                   \
-        if (bits)                                                                                          \
-            hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
-                               bits, (int)M, (int)N, (int)K);                                              \
-        else                                                                                               \
-            hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, sgn, \
-                               bits, (int)M, (int)N, (int)K);                                              \
-    } while (0)
+    hipLaunchKernelGGL((dense_f32_mfma_kernel<BN, V>), grid, dim3(256), 0, s, X, W, Y, (int)M, (int)N, (int)K)
     if (narrow && vec4)
         ESP_DENSE(32, true);
     else if (narrow)
