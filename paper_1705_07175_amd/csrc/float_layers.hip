@@ -3,9 +3,9 @@
 // their first dense / convolutional layer multiplies floats by +-1 weights.  These are
 // supporting kernels: LDS-tiled dense layers on the matrix cores (fp32 operands for the plain
 // product, three exact bf16 terms per input for the fused layer), a wave-per-output GEMV for
-// tiny batches, a direct
-// convolution with the filters transposed in LDS for general shapes, and the 3x3x3 first layer
-// of the CIFAR-10 network on the bf16 matrix cores (three exact terms per input as well).
+// tiny batches, a direct convolution with the filters transposed in LDS for general shapes,
+// and the 3x3x3 first layer of the CIFAR-10 network on the bf16 matrix cores (three exact
+// terms per input as well).
 #include "esp_internal.h"
 
 namespace esp {
