@@ -621,6 +621,27 @@ def test_dense_f32_bn_sign_pack(M, N, K):
     assert torch.equal(esp.dense_f32_bn_sign_pack(xd, wd, td, sd), bits)      # without `pre`
 
 
+@pytest.mark.parametrize("M", [3, 70, 600])
+def test_dense_f32_bn_sign_pack_wide_dynamic_range(M):
+    # signed inputs spread over six decades, exact zeros, values with all 24 significand bits set:
+    # the three-term bf16 kernel (M > 4) must stay within the fp32 tolerance like the streaming one
+    N, K = 200, 777
+    rng = np.random.default_rng(M)
+    x = (rng.standard_normal((M, K)) * 10.0 ** rng.uniform(-3, 3, size=(M, K))).astype(np.float32)
+    x[rng.random((M, K)) < 0.05] = 0.0
+    x[0, :8] = np.float32(1.9999999)       # 0x3fffffff: every significand bit set
+    x[0, 8:16] = np.float32(-16777215.0)   # 2^24 - 1
+    w = _pm1(rng, (N, K))
+    pre = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    thr, sgn = np.zeros(N, np.float32), np.ones(N, np.float32)
+    esp.dense_f32_bn_sign_pack(_f32(x), _f32(w), _f32(thr), _f32(sgn), pre=pre)
+    ref = oracle.dense_f64(x, w)
+    got = pre.cpu().numpy().astype(np.float64)
+    # error of a sum of K exact products accumulated in fp32, relative to the sum of magnitudes
+    scale = np.abs(x.astype(np.float64)).sum(axis=1, keepdims=True)
+    assert np.all(np.abs(got - ref) <= 1e-6 * scale + 1e-30)
+
+
 def test_bn_sign_pack_f32_bit_exact_on_given_preactivations():
     # Batch-norm + sign is folded on the host to a float threshold per channel that is exact
     # for every float input, so on the SAME float32 pre-activations the bits equal the
