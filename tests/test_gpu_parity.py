@@ -689,6 +689,20 @@ def test_conv_f32_bn_sign_pack_fused_equals_two_step():
             assert torch.equal(esp.conv_f32_bn_sign_pack(xd, fd, td, sd, stride, pad), two)
 
 
+def test_conv3x3x3_wide_dynamic_range():
+    # the 3x3x3 matrix-core path (three bf16 terms per input) on signed inputs spread over six
+    # decades: error of 27 exact products accumulated in fp32
+    rng = np.random.default_rng(11)
+    B, H, W, L2 = 2, 20, 37, 100
+    x = (rng.standard_normal((B, H, W, 3)) * 10.0 ** rng.uniform(-3, 3, size=(B, H, W, 3))).astype(np.float32)
+    x[0, 0, :4, :] = np.float32(1.9999999)
+    f = _pm1(rng, (L2, 3, 3, 3))
+    got = esp.conv_f32(_f32(x), _f32(f), 1, 1).cpu().numpy().astype(np.float64)
+    ref = oracle.conv_f64(x, f, 1, 1)
+    scale = oracle.conv_f64(np.abs(x), np.ones_like(f), 1, 1)      # sum of magnitudes per output
+    assert np.all(np.abs(got - ref) <= 1e-6 * scale + 1e-30)
+
+
 def test_xor_popcount_probe_counts_what_it_claims():
     # the measurement aid must really execute the pairs it reports: every lane's counter sum is
     # iters * sum_ij popcount(a_i ^ b_j) for the lane's seeded register values
