@@ -64,6 +64,19 @@ def _events_ms(fn, steps, warmup, torch):
     return start.elapsed_time(stop) / steps, wall_ms / steps
 
 
+def _median_ms(fn, steps, torch):
+    """Median milliseconds of ``steps`` calls of ``fn``, each bracketed by its own pair of HIP events
+    (so each sample also holds the few microseconds an event pair costs)."""
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in pairs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return t[len(t) // 2]
+
+
 def _hbm_entry(name, ms, algo_bytes, workload):
     gbs = algo_bytes / (ms * 1e-3) / 1e9
     return {"kernel": name, "workload": workload, "ms": round(ms, 5), "bound": "hbm",
@@ -220,6 +233,7 @@ def main() -> int:
         return 0
     if not args.no_extras:
         result["kernels"] = _supporting_kernels(torch, esp, synth, dev, np)
+        result["paper_configs"] = _paper_configs(torch, esp, synth, dev, args.steps, args.warmup)
         result["networks"] = _networks(torch, esp, nets, synth, dev)
         cnn = result["networks"]["bcnn"]
         result["bcnn_images_per_s"] = {
@@ -229,6 +243,8 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = _cpu_baseline(a_pm1, b_pm1, n, args.cpu_rows, np)
+        if not args.no_extras:
+            result["cpu_baseline"]["per_config_seconds"] = _cpu_per_config(synth)
 
     print(json.dumps(result))
     return 0
@@ -386,6 +402,42 @@ def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3)
     return out
 
 
+def _paper_configs(torch, esp, synth, dev, steps, warmup):
+    """The remaining sizes of the paper's evaluation that the other sections do not time: config 1
+    (one binary dense layer at batch 64, launch-latency-bound: microseconds only) and the smaller
+    squares of config 5, each on the XOR-popcount kernel and on the matrix cores."""
+    out = {}
+    a_pm1, b_pm1 = synth.config1()
+    m, k = a_pm1.shape
+    n = b_pm1.shape[0]
+    A = esp.pack_f32(torch.from_numpy(a_pm1).to(dev).to(torch.float32))
+    B = esp.pack_f32(torch.from_numpy(b_pm1).to(dev).to(torch.float32))
+    C = torch.empty((m, n), dtype=torch.int32, device=dev)
+    ms, wall = _events_ms(lambda: esp.bgemm(A, B, k, out=C), 200, 200, torch)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(20):
+            esp.bgemm(A, B, k, out=C)
+    ms_g, wall_g = _events_ms(graph.replay, 20, 20, torch)
+    out["config1_bgemm_64x1024x1024"] = {
+        "eager_us": round(1e3 * max(ms, wall), 2), "back_to_back_in_a_graph_us": round(1e3 * max(ms_g, wall_g) / 20, 2),
+        "note": "0.13 Gbop: bound by launch latency, no roofline fraction is meaningful"}
+    for size in (2048, 4096):
+        a_pm1, b_pm1 = synth.config5_square(size)
+        A = esp.pack_f32(torch.from_numpy(a_pm1).to(dev).to(torch.float32))
+        B = esp.pack_f32(torch.from_numpy(b_pm1).to(dev).to(torch.float32))
+        C = torch.empty((size, size), dtype=torch.int32, device=dev)
+        bop = 2.0 * size ** 3
+        ms, _ = _events_ms(lambda: esp.bgemm(A, B, size, out=C), steps, warmup, torch)
+        ms_m, _ = _events_ms(lambda: esp.bgemm_mfma(A, B, size, out=C), steps, warmup, torch)
+        tb = bop / (ms * 1e-3) / 1e12
+        out["config5_bgemm_%d_cube" % size] = {
+            "ms": round(ms, 5), "tbops": round(tb, 2), "frac_of_valu_peak": round(tb / VALU_PEAK_TBOPS, 4),
+            "mfma_alternative_ms": round(ms_m, 5), "mfma_alternative_tbops": round(bop / (ms_m * 1e-3) / 1e12, 2)}
+        del A, B, C
+    return out
+
+
 def _networks(torch, esp, nets, synth, dev, only=None):
     """images/s of the two networks; batch 1 is timed both eagerly and as a replayed HIP graph."""
     res = {"bmlp": {}, "bcnn": {}}
@@ -401,6 +453,7 @@ def _networks(torch, esp, nets, synth, dev, only=None):
             net.forward(x)
         ms_g, wall_g = _events_ms(graph.replay, steps, warm, torch)
         entry["graph_ms"] = round(max(ms_g, wall_g), 5)
+        entry["graph_median_ms"] = round(_median_ms(graph.replay, max(steps, 100), torch), 5)
         best = min(entry["eager_ms"], entry["graph_ms"])
         entry["images_per_s"] = round(batch / (best * 1e-3), 1)
         return entry
@@ -464,6 +517,41 @@ def _cpu_baseline(a_pm1, b_pm1, n, sample_rows, np):
     return {"value": round(gbops, 2), "unit": "Gbop/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d output rows (all N, all K) of the same product, %.1f s; "
                       "full job extrapolated linearly: %.0f s" % (rows, n, dt, 2.0 * n**3 / (gbops * 1e9))}
+
+
+def _cpu_per_config(synth):
+    """Seconds the oracle takes on the paper-sized configurations it finishes whole, on one thread
+    and on all host threads (the larger ones are covered by the sampled headline figure)."""
+    import oracle
+    from oracle import nets as onets
+
+    def seconds(fn):
+        t0 = time.perf_counter()
+        fn()
+        return round(time.perf_counter() - t0, 4)
+
+    a1, b1 = synth.config1()
+    x2, f2, bn2 = synth.config2()
+    mlp = synth.mlp_params()
+    cnn = synth.cnn_params()
+    a5, b5 = synth.config5_square(2048)
+    jobs = (
+        ("config1_dense_64x1024x1024", lambda: oracle.dense_pm1(a1, b1)),
+        ("config2_conv_bn_sign_batch32", lambda: oracle.bn_sign(oracle.conv_pm1(x2, f2, 1, 1), bn2, synth.BN_EPS)),
+        ("config3_mlp_batch1", lambda: onets.mlp_forward(synth.mlp_input(1), mlp, synth.BN_EPS)),
+        ("config3_mlp_batch64", lambda: onets.mlp_forward(synth.mlp_input(64), mlp, synth.BN_EPS)),
+        ("config4_cnn_batch1", lambda: onets.cnn_forward(synth.cnn_input(1), cnn, synth.BN_EPS)),
+        ("config5_dense_2048_cube", lambda: oracle.dense_pm1(a5, b5)),
+    )
+    threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
+    out = {"threads": threads}
+    for name, fn in jobs:
+        oracle.set_threads(1)
+        one = seconds(fn)
+        oracle.set_threads(threads)
+        out[name] = {"one_thread": one, "all_threads": seconds(fn)}
+    oracle.set_threads(1)
+    return out
 
 
 if __name__ == "__main__":
