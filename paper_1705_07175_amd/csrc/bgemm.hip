@@ -151,6 +151,26 @@ struct StoreSignBits {
         return LaneWord{ty + TY * (tx & 7), tx >> 3, true, lo, hi};
     }
 
+    // 8 x 4 counters per lane: the tile is one word wide, a lane's register holds one nibble
+    // for each of its 8 rows
+    template <int TY>
+    __device__ __forceinline__ LaneWord tile_8x4(const int (&acc)[8][4], const int (&lim)[4], int tx, int ty) const
+    {
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                x |= acc[i][c] <= lim[c] ? 1u << (4 * i + c) : 0u;
+        x = nibble_swap<1>(x, tx & 1);
+        x = nibble_swap<2>(x, tx & 2);
+        x = nibble_swap<4>(x, tx & 4);
+        // lane tx now holds, of row ty + TY*(tx % 8), the 32 bits that belong to the 8 lanes of
+        // its half: lanes 0-7 the low half of the word, lanes 8-15 the high half
+        const uint32_t other = lane_xor<8>(x);
+        return LaneWord{ty + TY * (tx & 7), 0, tx < 8, x, other};
+    }
+
     // TM x 4 counters per lane (TM = 1, 2 or 4): one word per row i < TM
     template <int TY, int TM>
     __device__ __forceinline__ LaneWord tile(const int (&acc)[TM][4], const int (&lim)[4], int tx, int ty) const
@@ -351,8 +371,10 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
                 lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
         }
         LaneWord lw;
-        if constexpr (TM == 8)
+        if constexpr (TM == 8 && TN == 8)
             lw = bits.template tile<TY>(acc, lim, tx, ty);
+        else if constexpr (TM == 8)
+            lw = bits.template tile_8x4<TY>(acc, lim, tx, ty);
         else
             lw = bits.template tile<TY, TM>(acc, lim, tx, ty);
         const int w = (n0 >> 6) + lw.wl;
@@ -414,8 +436,9 @@ static int launch_tile2(const ASrc &asrc, const uint32_t *b, const TileOut &o, i
     return launch_status();
 }
 
-// Tile shape: 128x128 (8x8 counters per lane) when that still gives every CU two blocks,
-// otherwise 64x64 (4x4 per lane), which keeps small-N / small-M products spread out.
+// Tile shape: 128x128 (8x8 counters per lane) when that still gives every CU two blocks, else
+// 128x64 (8x4) under the same condition, otherwise 64x64 (4x4 per lane) or 32x64, which keep
+// small-N / small-M products spread out.
 template <class ASrc, bool VEC16B>
 static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
                        int64_t K_true, int64_t row_dw, hipStream_t stream)
@@ -425,6 +448,9 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
     const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
     if (big_tiles >= 512 || quantum > 64)
         return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    // half as wide while that gives every CU its two blocks
+    if (ceil_div(M, 128) * ceil_div(N, 64) >= 512)
+        return launch_tile2<128, 64, 8, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     // small products (dense layers at moderate batch, convolutions at batch 1): halve the
     // rows per lane so that twice as many waves share the work when the chip is not full
     if (ceil_div(M, 64) * ceil_div(N, 64) >= 256 || quantum > 32)

@@ -141,10 +141,11 @@ def test_bgemm_large_tile_path_full():
 
 # every length of the last K stage (1 to 8 k-groups of 128 bits, handled two at a time with an odd
 # one at the end), an odd number of words per row (8-byte loads) and a K that is not a multiple of
-# 64, on each of the three tile shapes
+# 64, on each of the four tile shapes (32x64, 64x64, 128x64, 128x128)
 @pytest.mark.parametrize("M,N,Ks", [
     (130, 70, (1088, 1152, 1280, 1344, 1472, 1600, 1728, 1856, 1984, 2048, 2112, 1100, 960, 64)),
     (1100, 1100, (1152, 1280, 1472, 1728, 1984, 2112, 1100)),
+    (2100, 1990, (1152, 1344, 1600, 2112, 1100, 64)),
     (2900, 2950, (1152, 1344, 1600, 2112)),
 ])
 def test_bgemm_tile_k_tails(M, N, Ks):
@@ -370,9 +371,9 @@ def test_bgemm_bn_sign_pack_few_rows(M, N, K):
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
-@pytest.mark.parametrize("engine", [0, 1])
-def test_bgemm_bn_sign_pack_large_tiles(engine):
-    M, N, K = 2900, 2950, 640
+@pytest.mark.parametrize("engine,M,N,K", [(0, 2900, 2950, 640), (1, 2900, 2950, 640),
+                                          (0, 2100, 1990, 640), (0, 32768 + 70, 100, 1152)])   # 128x64 tiles
+def test_bgemm_bn_sign_pack_large_tiles(engine, M, N, K):
     rng = np.random.default_rng(77)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
     bnp = synth.bn_params(rng, N)
@@ -387,6 +388,7 @@ def test_bgemm_bn_sign_pack_large_tiles(engine):
 FUSED_CONV_CASES = CONV_CASES + [
     (2, 32, 32, 128, 128, 3, 3, 1, 1),     # implicit gather, 64x64 tiles
     (40, 32, 32, 128, 256, 3, 3, 1, 1),    # implicit gather, 128x128 tiles, several K stages
+    (33, 32, 32, 128, 100, 3, 3, 1, 1),    # implicit gather, 128x64 tiles, partial word
     (3, 7, 9, 256, 100, 3, 3, 2, 1),
     (2, 5, 5, 384, 64, 3, 3, 1, 1),
 ]
@@ -421,6 +423,7 @@ POOL_CONV_CASES = [
     (1, 16, 16, 256, 256, 3, 3, 1, 1),     # W2 = 16: 32-row tiles
     (3, 8, 8, 512, 512, 3, 3, 1, 1),       # W2 = 8
     (40, 32, 32, 128, 256, 3, 3, 1, 1),    # 128-row tiles, several K stages
+    (32, 32, 32, 128, 128, 3, 3, 1, 1),    # 128x64 tiles (one word wide)
     (5, 16, 16, 128, 100, 3, 3, 1, 1),     # partial last word, ragged tile count
     (3, 4, 2, 128, 70, 3, 3, 1, 1),        # W2 = 2, H2 = 4
     (2, 16, 8, 128, 64, 3, 3, 2, 1),       # stride 2: H2 = 8, W2 = 4
