@@ -18,6 +18,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "espresso_oracle.c")
 _LIB = os.path.join(_HERE, "libespresso_oracle.so")
+# The pin tests check themselves by running against deliberately broken builds of the C
+# source (tests/test_oracle_mutations.py); this variable points the loader at such a build.
+_LIB_OVERRIDE = os.environ.get("ESPRESSO_ORACLE_LIB")
 
 _lib = None
 
@@ -39,8 +42,11 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        if _LIB_OVERRIDE:
+            _lib = ctypes.CDLL(_LIB_OVERRIDE)
+        else:
+            build()
+            _lib = ctypes.CDLL(_LIB)
         _lib.orc_mismatches_words.restype = ctypes.c_int64
         _lib.orc_bn_value.restype = ctypes.c_double
         _lib.orc_bn_value.argtypes = [ctypes.c_double] + [ctypes.c_float] * 5
