@@ -386,7 +386,8 @@ def test_bgemm_bn_sign_pack_large_tiles(engine, M, N, K):
 
 
 FUSED_CONV_CASES = CONV_CASES + [
-    (2, 32, 32, 128, 128, 3, 3, 1, 1),     # implicit gather, 64x64 tiles
+    (2, 32, 32, 128, 128, 3, 3, 1, 1),     # implicit gather, 32x64 tiles
+    (8, 32, 32, 128, 128, 3, 3, 1, 1),     # implicit gather, 64x64 tiles
     (40, 32, 32, 128, 256, 3, 3, 1, 1),    # implicit gather, 128x128 tiles, several K stages
     (33, 32, 32, 128, 100, 3, 3, 1, 1),    # implicit gather, 128x64 tiles, partial word
     (3, 7, 9, 256, 100, 3, 3, 2, 1),
