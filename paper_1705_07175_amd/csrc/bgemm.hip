@@ -436,9 +436,14 @@ static int launch_tile2(const ASrc &asrc, const uint32_t *b, const TileOut &o, i
     return launch_status();
 }
 
-// Tile shape: 128x128 (8x8 counters per lane) when that still gives every CU two blocks, else
-// 128x64 (8x4) under the same condition, otherwise 64x64 (4x4 per lane) or 32x64, which keep
-// small-N / small-M products spread out.
+// Tile shape.  Every CU should get at least two blocks: 128x128 (8x8 counters per lane, two
+// waves per SIMD) or 128x64 (8x4, three waves per SIMD) while 512 of them exist, otherwise
+// 64x64 (4x4) or 32x64, which keep small-N / small-M products spread out.  Between the two
+// large shapes the source of A decides (measured): rows of a packed matrix are cheap to fetch
+// and the narrower tile, whose third wave fills the other two's waits, is 2.5 % faster on an
+// 8192-cube; rows gathered from an NHWC input cost address arithmetic per row and stage, and a
+// tile half as wide fetches every row twice as often (3-7 % slower on 3x3 convolutions over
+// 256 and 512 channels).
 template <class ASrc, bool VEC16B>
 static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, int64_t M, int64_t N,
                        int64_t K_true, int64_t row_dw, hipStream_t stream)
@@ -446,10 +451,10 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
     // a fused 2x2 pool needs whole pairs of image rows in a tile: BM a multiple of 2 * W2
     const int quantum = o.pool_log2w ? 2 << o.pool_log2w : 1;
     const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
-    if (big_tiles >= 512 || quantum > 64)
+    const bool narrow_fills = ceil_div(M, 128) * ceil_div(N, 64) >= 512;
+    if (ASrc::kGathered ? (big_tiles >= 512 || quantum > 64) : (quantum > 64 || (big_tiles >= 512 && !narrow_fills)))
         return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
-    // half as wide while that gives every CU its two blocks
-    if (ceil_div(M, 128) * ceil_div(N, 64) >= 512)
+    if (narrow_fills)
         return launch_tile2<128, 64, 8, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     // small products (dense layers at moderate batch, convolutions at batch 1): halve the
     // rows per lane so that twice as many waves share the work when the chip is not full

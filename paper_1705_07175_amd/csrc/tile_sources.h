@@ -51,6 +51,7 @@ __device__ __forceinline__ uint4 load_chunk_raw(const uint32_t *__restrict__ p, 
 // ---- A operand: rows of a packed matrix ------------------------------------------
 template <bool VEC16>
 struct MatrixA {
+    static constexpr bool kGathered = false;   // a row is one contiguous run of memory
     const uint32_t *base;
     int rows;    // M
     int row_dw;  // dwords per row
@@ -79,6 +80,7 @@ struct MatrixA {
 // tap = kd / cdw = dy*kw + dx; pixels outside the image read as zero words (= -1).
 // Needs cdw % 4 == 0 (C a multiple of 128) so that a 16-byte chunk never straddles taps.
 struct ConvA {
+    static constexpr bool kGathered = true;    // a row is kh * kw runs found by index arithmetic
     const uint32_t *in;
     int rows;    // B*H2*W2
     int row_dw;  // kh*kw*cdw
