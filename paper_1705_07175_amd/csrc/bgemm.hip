@@ -7,10 +7,12 @@
 //    keeps a TM x TN tile of int32 mismatch counters in registers and runs a pure
 //    v_xor_b32 / v_bcnt_u32_b32 (accumulating popcount) inner loop on 32-bit halves
 //    of the words.  Two LDS stage buffers (one barrier per stage), global loads one
-//    stage ahead, LDS operand reads one k-group ahead: a wave that waits leaves its
-//    SIMD to the one other wave, which runs at its own fixed pace.  The paper's own design (shared-memory tiles + register blocking,
-//    Sec. 5.2 "Efficient Matrix multiplication") is kept; tile shapes, the LDS
-//    layout and the block order are chosen for 64-wide wavefronts and 8 XCDs.
+//    stage ahead, LDS operand reads one k-group ahead: every wave runs at its own fixed
+//    pace, so what it waits for is lost unless another wave of its SIMD fills the gap
+//    (8 x 4 counters per lane leave room for three waves per SIMD, 8 x 8 for two).
+//    The paper's own design (shared-memory tiles + register blocking, Sec. 5.2
+//    "Efficient Matrix multiplication") is kept; tile shapes, the LDS layout and the
+//    block order are chosen for 64-wide wavefronts and 8 XCDs.
 //    The A operand comes either from a packed matrix or, for convolutions, straight
 //    from the packed NHWC input (the unrolling of Sec. 5.2 / Fig. 3 done by the
 //    loader: the lowered matrix never exists in memory).  The epilogue writes either
