@@ -154,7 +154,7 @@ def main() -> int:
         return 1
 
     # what the vector ALUs sustain on the bare xor + popcount loop (registers only)
-    blocks, iters = 2 * CUS, 2000        # two waves per SIMD, as the tiled kernel runs
+    blocks, iters = 2 * CUS, 2000        # two waves per SIMD: where the bare loop is fastest
     sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
     probe_bop = esp.xor_popcount_probe(sink, blocks, iters)
     ms_p, _ = _events_ms(lambda: esp.xor_popcount_probe(sink, blocks, iters), 20, 10, torch)
