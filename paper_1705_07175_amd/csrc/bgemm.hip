@@ -454,8 +454,10 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
     const int quantum = o.pool_log2w ? 2 << o.pool_log2w : 1;
     const int64_t big_tiles = ceil_div(M, 128) * ceil_div(N, 128);
     const bool narrow_fills = ceil_div(M, 128) * ceil_div(N, 64) >= 512;
-    if (ASrc::kGathered ? (big_tiles >= 512 || quantum > 64) : (quantum > 64 || (big_tiles >= 512 && !narrow_fills)))
-        return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    if constexpr (ASrc::kGathered) {     // (only convolutions pool, so quantum is 1 otherwise)
+        if (big_tiles >= 512 || quantum > 64)
+            return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
+    }
     if (narrow_fills)
         return launch_tile2<128, 64, 8, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     // small products (dense layers at moderate batch, convolutions at batch 1): halve the

@@ -131,7 +131,7 @@ def test_bgemm_config1():
 
 
 def test_bgemm_large_tile_path_full():
-    # enough 128x128 tiles to take the large-tile kernel, ragged in M and N, several K stages
+    # enough tiles for the large-tile kernel (128x64 on packed matrices), ragged in M and N, several K stages
     M, N, K = 2900, 2950, 2240
     rng = np.random.default_rng(5)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
@@ -141,7 +141,8 @@ def test_bgemm_large_tile_path_full():
 
 # every length of the last K stage (1 to 8 k-groups of 128 bits, handled two at a time with an odd
 # one at the end), an odd number of words per row (8-byte loads) and a K that is not a multiple of
-# 64, on each of the four tile shapes (32x64, 64x64, 128x64, 128x128)
+# 64, on each tile shape a packed-matrix product can take (32x64, 64x64, 128x64; 128x128 serves
+# convolutions and is covered by the fused convolution cases)
 @pytest.mark.parametrize("M,N,Ks", [
     (130, 70, (1088, 1152, 1280, 1344, 1472, 1600, 1728, 1856, 1984, 2048, 2112, 1100, 960, 64)),
     (1100, 1100, (1152, 1280, 1472, 1728, 1984, 2112, 1100)),
