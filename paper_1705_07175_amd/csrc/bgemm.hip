@@ -296,14 +296,23 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
             acc[i][j] = 0;
 
     // thresholds of the lane's columns.  The small tiles serve products whose time is a chain
-    // of memory latencies, so they fetch them now, alongside the first stage; the large tile
-    // keeps its registers for the main loop and fetches them in the epilogue.
+    // of memory latencies, so they fetch them now, alongside the first stage, and keep them in
+    // registers; the large tiles need their registers for the main loop: their limits and flip
+    // words are fetched now as well, but wait in LDS for the epilogue, which then starts
+    // without a trip to memory.
     constexpr bool kEarlyLimits = BITS && TM < 8;
     int lim[BITS ? TN : 1];
+    __shared__ __align__(16) int lim_s[(BITS && !kEarlyLimits) ? BN : 4];
+    __shared__ uint64_t flip_s[(BITS && !kEarlyLimits) ? BN / 64 : 1];
     if constexpr (kEarlyLimits) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
             lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+    } else if constexpr (BITS) {
+        for (int c = tid; c < BN; c += NT)
+            lim_s[c] = bits.mismatch_limit(n0 + c, N, K_true);
+        if (tid < BN / 64)
+            flip_s[tid] = (n0 >> 6) + tid < bits.Nw ? bits.flip[(n0 >> 6) + tid] : 0ull;
     }
 
     const int stages = (row_dw + kStageDw - 1) / kStageDw;
@@ -369,8 +378,13 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         static_assert(TX == 16, "a 64-column word is spread over 16 lanes x 4 columns");
         if constexpr (!kEarlyLimits) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                lim[j] = bits.mismatch_limit(n0 + (j / 4) * 4 * TX + tx * 4 + j % 4, N, K_true);
+            for (int jg = 0; jg < TN / 4; ++jg) {
+                const int4 l4 = *reinterpret_cast<const int4 *>(&lim_s[jg * 4 * TX + tx * 4]);
+                lim[jg * 4 + 0] = l4.x;
+                lim[jg * 4 + 1] = l4.y;
+                lim[jg * 4 + 2] = l4.z;
+                lim[jg * 4 + 3] = l4.w;
+            }
         }
         LaneWord lw;
         if constexpr (TM == 8 && TN == 8)
@@ -380,7 +394,11 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         else
             lw = bits.template tile<TY, TM>(acc, lim, tx, ty);
         const int w = (n0 >> 6) + lw.wl;
-        const uint64_t word = bits.finish(lw, w);
+        uint64_t word;
+        if constexpr (kEarlyLimits)
+            word = bits.finish(lw, w);
+        else
+            word = lw.have ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flip_s[lw.wl]) : 0ull;   // flip_s is 0 beyond Nw
         if (bits.pool_log2w == 0) {
             if (lw.have && m0 + lw.rl < M && w < bits.Nw)
                 bits.out[(int64_t)(m0 + lw.rl) * bits.Nw + w] = word;
