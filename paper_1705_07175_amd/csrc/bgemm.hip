@@ -260,6 +260,7 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         brow[i] = B + (int64_t)min(n0 + (tid + i * NT) / kKG, N - 1) * row_dw;
     uint4 pa[A_CH], pb[B_CH];
     bool ka[A_CH], kb;     // whether a chunk counts; applied when it moves to LDS
+    bool whole;            // the fetched stage has no K tail
 
     auto prefetch = [&](int stage) {
         const int kd = stage * kStageDw + kg_mine * 4;
@@ -273,18 +274,32 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         for (int i = 0; i < B_CH; ++i)
             pb[i] = load_chunk_raw<VEC16B>(brow[i], kd, row_dw);
         kb = kd < row_dw;
+        whole = (stage + 1) * kStageDw <= row_dw;
     };
 
+    // A stage of a packed-matrix product that lies inside the rows altogether (uniform over the
+    // block) needs no K-tail mask; a gathered A masks its border pixels in every stage.
     auto commit = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            As[buf][kg_mine][(tid + i * NT) / kKG] = keep4(pa[i], ka[i]);
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
+        auto store_b = [&](int i, const uint4 v) {
             const int nl = (tid + i * NT) / kKG;
             // column nl is register column j of lane tx: nl = (j/4)*(4*TX) + tx*4 + j%4
             const int j = (nl / (4 * TX)) * 4 + nl % 4;
-            Bs[buf][kg_mine][j * TX + (nl % (4 * TX)) / 4] = keep4(pb[i], kb);
+            Bs[buf][kg_mine][j * TX + (nl % (4 * TX)) / 4] = v;
+        };
+        if (!ASrc::kGathered && whole) {       // uniform over the block
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i)
+                As[buf][kg_mine][(tid + i * NT) / kKG] = pa[i];
+#pragma unroll
+            for (int i = 0; i < B_CH; ++i)
+                store_b(i, pb[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i)
+                As[buf][kg_mine][(tid + i * NT) / kKG] = keep4(pa[i], ka[i]);
+#pragma unroll
+            for (int i = 0; i < B_CH; ++i)
+                store_b(i, keep4(pb[i], kb));
         }
     };
 
