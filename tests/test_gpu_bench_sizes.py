@@ -120,3 +120,44 @@ def test_conv1_batch256_sampled_images():
     assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(1.0, np.abs(ref)))
     want_bits = oracle.pack_bits(oracle.bn_sign(got.astype(np.float64), layers[0]["bn"], synth.BN_EPS))
     assert np.array_equal(_words_np(bits)[idx], want_bits)
+
+
+# ---- beyond 2^31 elements: element offsets no longer fit 32 bits -------------------------------
+def test_bgemm_output_beyond_2_to_31_elements():
+    # C has 140000 x 16384 = 2.29e9 int32 values (9.2 GB); K = 64 keeps the product itself small
+    M, N, K = 140000, 16384, 64
+    g = _gen(20)
+    A = _rand_words((M, 1), g)
+    B = _rand_words((N, 1), g)
+    C = esp.bgemm(A, B, K)
+    rows = _sample(M, 6, 20)
+    a = oracle.unpack_bits(_words_np(A[torch.from_numpy(rows).to(DEV)]), K)
+    b = oracle.unpack_bits(_words_np(B), K)
+    assert np.array_equal(C[torch.from_numpy(rows).to(DEV)].cpu().numpy(), oracle.dense_pm1(a, b))
+    del C
+    torch.cuda.empty_cache()
+
+
+def test_pack_f32_beyond_2_to_31_elements():
+    rows, k = 70000, 32768           # 2.29e9 floats (9.2 GB)
+    x = torch.rand((rows, k), device=DEV, generator=_gen(21)) - 0.5
+    out = esp.pack_f32(x)
+    idx = _sample(rows, 5, 21)
+    xs = x[torch.from_numpy(idx).to(DEV)].cpu().numpy()
+    assert np.array_equal(_words_np(out[torch.from_numpy(idx).to(DEV)]), oracle.pack_bits(oracle.sign(xs)))
+    del x, out
+    torch.cuda.empty_cache()
+
+
+def test_bn_sign_pack_beyond_2_to_31_elements():
+    rows, c = 18 * 1024 * 1024, 128  # 2.42e9 int32 values (9.7 GB)
+    x = torch.randint(-1152, 1153, (rows, c), device=DEV, generator=_gen(22), dtype=torch.int32)
+    bnp = synth.bn_params(np.random.default_rng(22), c)
+    bnp = (bnp[0], bnp[1], (bnp[2] * 30).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    out = esp.bn_sign_pack(x, torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV))
+    idx = _sample(rows, 6, 22)
+    xs = x[torch.from_numpy(idx).to(DEV)].cpu().numpy()
+    assert np.array_equal(_words_np(out[torch.from_numpy(idx).to(DEV)]), oracle.pack_bits(oracle.bn_sign(xs, bnp, synth.BN_EPS)))
+    del x, out
+    torch.cuda.empty_cache()
