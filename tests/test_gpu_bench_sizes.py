@@ -161,3 +161,17 @@ def test_bn_sign_pack_beyond_2_to_31_elements():
     assert np.array_equal(_words_np(out[torch.from_numpy(idx).to(DEV)]), oracle.pack_bits(oracle.bn_sign(xs, bnp, synth.BN_EPS)))
     del x, out
     torch.cuda.empty_cache()
+
+
+def test_bgemm_mfma_output_beyond_2_to_31_elements():
+    M, N, K = 140000, 16384, 128
+    g = _gen(23)
+    A = _rand_words((M, 2), g)
+    B = _rand_words((N, 2), g)
+    C = esp.bgemm_mfma(A, B, K)
+    rows = _sample(M, 6, 23)
+    a = oracle.unpack_bits(_words_np(A[torch.from_numpy(rows).to(DEV)]), K)
+    b = oracle.unpack_bits(_words_np(B), K)
+    assert np.array_equal(C[torch.from_numpy(rows).to(DEV)].cpu().numpy(), oracle.dense_pm1(a, b))
+    del C
+    torch.cuda.empty_cache()
