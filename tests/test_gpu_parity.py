@@ -76,7 +76,7 @@ BGEMM_SHAPES = [
     (9, 10, 4096), (64, 1024, 1024), (130, 70, 200), (257, 513, 1152),       # 64x64 tiles
     (100, 1000, 64), (65, 129, 4608), (1024, 10, 1024), (300, 301, 8256),
     (1024, 10, 4096), (100, 16, 200), (9, 1, 64), (300, 8, 8256), (64, 9, 8192), (2000, 3, 70),   # few columns
-    (33, 17, 128),
+    (33, 17, 128), (3, 5, 1), (70, 70, 1),                                      # a single bit per row
 ]
 
 
