@@ -286,6 +286,14 @@ int esp_conv_f32(const float *in, const float *filt, float *out,
 /* dense_f32_bn_sign_pack: esp_dense_f32 followed by esp_bn_sign_pack_f32 in  */
 /* one kernel; `bits` uint64 [M][ceil(N/64)] is always written, `pre` (float  */
 /* [M][N], the pre-activations) only if not NULL.                             */
+/*                                                                            */
+/* dense_f32_bw_bn_sign_pack: the same layer with its +-1 weights bit-packed  */
+/* (Wbits uint64 [N][ceil(K/64)] as esp_pack_f32 writes them: bit 1 = +1,     */
+/* zero tail; Sec. 6.2 "Binary optimized layers": weights are packed once at  */
+/* load time) -- 1/32 of the weight memory and traffic, which is most of what */
+/* this layer costs when a network is evaluated one input at a time.  The     */
+/* pre-activations are fp32 sums of +-x[k] (same tolerance as the float form, */
+/* the summation order differs).  K < 2^30.                                   */
 /* ------------------------------------------------------------------------- */
 int esp_bn_fold_f32(const float *gamma, const float *beta, const float *mean, const float *var,
                     float eps, int C, float *thr, float *sgn);
@@ -296,6 +304,10 @@ int esp_bn_sign_pack_f32(const float *x, const float *thr, const float *sgn,
 int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const float *thr, const float *sgn,
                                uint64_t *bits, float *pre, int64_t M, int64_t N, int64_t K,
                                esp_stream stream);
+
+int esp_dense_f32_bw_bn_sign_pack(const float *X, const uint64_t *Wbits, const float *thr,
+                                  const float *sgn, uint64_t *bits, float *pre, int64_t M, int64_t N,
+                                  int64_t K, esp_stream stream);
 
 int esp_conv_f32_bn_sign_pack(const float *in, const float *filt, const float *thr, const float *sgn,
                               uint64_t *bits, float *pre,

@@ -30,7 +30,7 @@ EXPORTS = (
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
     "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2", "esp_dense_f32_bn_sign_pack",
-    "esp_xor_popcount_probe", "esp_bitplane_dense",
+    "esp_xor_popcount_probe", "esp_bitplane_dense", "esp_dense_f32_bw_bn_sign_pack",
 )
 
 _lib = None
@@ -81,6 +81,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_pool2_fusable.argtypes = [i32] * 7
         l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
         l.esp_dense_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        l.esp_dense_f32_bw_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_xor_popcount_probe.argtypes = [vp, i32, i32, vp, vp]
         l.esp_bitplane_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_version.argtypes = []
@@ -376,6 +377,26 @@ def dense_f32_bn_sign_pack(x: torch.Tensor, w: torch.Tensor, thr: torch.Tensor, 
     _check(lib().esp_dense_f32_bn_sign_pack(px, pw, _dev(thr, torch.float32, "thr"), _dev(sgn, torch.float32, "sgn"),
                                             _dev(out, PACKED, "out"), ppre, M, N, K, _stream()),
            "esp_dense_f32_bn_sign_pack")
+    return out
+
+
+def dense_f32_bw_bn_sign_pack(x: torch.Tensor, wbits: torch.Tensor, thr: torch.Tensor, sgn: torch.Tensor,
+                              out: torch.Tensor | None = None, pre: torch.Tensor | None = None) -> torch.Tensor:
+    """``esp_dense_f32_bw_bn_sign_pack``: the float dense layer with bit-packed +-1 weights
+    (``wbits`` packed [N][ceil(K/64)] as from ``pack_f32``) + folded batch-norm + sign."""
+    px, pw = _dev(x, torch.float32, "x"), _dev(wbits, PACKED, "wbits")
+    M, K = x.shape
+    N = wbits.shape[0]
+    if wbits.dim() != 2 or wbits.shape[1] != words(K) or thr.numel() != N or sgn.numel() != N:
+        raise ValueError("shape mismatch")
+    out = _out(out, (M, words(N)), PACKED, x.device)
+    if pre is not None:
+        _out(pre, (M, N), torch.float32, x.device)
+    ppre = _dev(pre, torch.float32, "pre") if pre is not None else None
+    _check(lib().esp_dense_f32_bw_bn_sign_pack(px, pw, _dev(thr, torch.float32, "thr"),
+                                               _dev(sgn, torch.float32, "sgn"), _dev(out, PACKED, "out"), ppre,
+                                               M, N, K, _stream()),
+           "esp_dense_f32_bw_bn_sign_pack")
     return out
 
 

@@ -55,12 +55,18 @@ __device__ __forceinline__ void split3(const float4 v, uint2 &hi, uint2 &mid, ui
     lo = make_uint2(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]));
 }
 
-template <int BM, int G, bool VEC4, bool FUSE>
+// WBITS: the weights arrive bit-packed ([N][ceil(K/64)] words as from esp_pack_f32, bit 1 = +1):
+// a thread fetches the dword that holds the four bits of its unit and expands them to +-1 bf16
+// values on the way to LDS (1/32 of the weight traffic).
+template <int BM, int G, bool VEC4, bool FUSE, bool WBITS>
 __global__ __launch_bounds__(256)
-void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ Wt, float *__restrict__ Y,
+void dense_bf16x3_kernel(const float *__restrict__ X, const void *__restrict__ Wv, float *__restrict__ Y,
                          const float *__restrict__ thr, const float *__restrict__ sgn,
                          uint64_t *__restrict__ bits, int M, int N, int K)
 {
+    const float *__restrict__ Wt = static_cast<const float *>(Wv);
+    const uint32_t *__restrict__ Wb = static_cast<const uint32_t *>(Wv);
+    const int wrow_dw = 2 * ((K + 63) / 64);
     constexpr int BN = 64 * G, BK = 64, PITCH = 72;       // bf16 elements per LDS row (144 bytes)
     constexpr int FM = BM / 64;                           // 32-row blocks per wave
     constexpr int XQ = BM * BK / 4 / 256, WQ = BN * BK / 4 / 256;
@@ -72,7 +78,8 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
     // unit u = tid + i * 256 -> row u / 16, k offset 4 * (u % 16): 16 lanes read 256 contiguous
     // bytes; rows beyond the matrix read the last row (their results are not stored), the K tail
     // reads 0
-    float4 xr[XQ], wr[WQ];
+    float4 xr[XQ], wr[WBITS ? 1 : WQ];
+    uint32_t wdw[WBITS ? WQ : 1];
     auto fetch = [&](const float *base, int row, int rows, int k0, int u) {
         const int r = min(row + u / 16, rows - 1), k = k0 + 4 * (u % 16);
         const float *p = base + (int64_t)r * K;
@@ -93,8 +100,13 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
         for (int i = 0; i < XQ; ++i)
             xr[i] = fetch(X, m0, M, k0, tid + i * 256);
 #pragma unroll
-        for (int i = 0; i < WQ; ++i)
-            wr[i] = fetch(Wt, n0, N, k0, tid + i * 256);
+        for (int i = 0; i < WQ; ++i) {
+            const int u = tid + i * 256;
+            if constexpr (WBITS)   // k0 is a multiple of 64 < K, so the dword lies inside the row
+                wdw[i] = Wb[(int64_t)min(n0 + u / 16, N - 1) * wrow_dw + (k0 + 4 * (u % 16)) / 32];
+            else
+                wr[i] = fetch(Wt, n0, N, k0, u);
+        }
     };
     auto commit = [&]() {
 #pragma unroll
@@ -109,10 +121,19 @@ void dense_bf16x3_kernel(const float *__restrict__ X, const float *__restrict__ 
 #pragma unroll
         for (int i = 0; i < WQ; ++i) {
             const int u = tid + i * 256, r = u / 16, k = 4 * (u % 16);
-            const float4 w = wr[i];
-            *reinterpret_cast<uint2 *>(&Ws[r][k]) =
-                make_uint2(pack_hi16(__float_as_uint(w.x), __float_as_uint(w.y)),
-                           pack_hi16(__float_as_uint(w.z), __float_as_uint(w.w)));
+            if constexpr (WBITS) {
+                // bit b -> bf16 +1 (0x3F80) or -1 (0xBF80); beyond K the inputs are 0, so the
+                // value there does not matter
+                const uint32_t nib = wdw[i] >> (k % 32);
+                *reinterpret_cast<uint2 *>(&Ws[r][k]) =
+                    make_uint2(0xBF80BF80u ^ ((nib & 1u) << 15) ^ ((nib & 2u) << 30),
+                               0xBF80BF80u ^ ((nib & 4u) << 13) ^ ((nib & 8u) << 28));
+            } else {
+                const float4 w = wr[i];
+                *reinterpret_cast<uint2 *>(&Ws[r][k]) =
+                    make_uint2(pack_hi16(__float_as_uint(w.x), __float_as_uint(w.y)),
+                               pack_hi16(__float_as_uint(w.z), __float_as_uint(w.w)));
+            }
         }
     };
 
@@ -407,6 +428,95 @@ void dense_f32_gemv_bits_kernel(const float *__restrict__ X, const float *__rest
                 for (int j = 0; j < NPW; ++j)
                     acc[j][m] = fmaf(x, w[j], acc[j][m]);
             }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NPW; ++j) {
+        const int n = n_blk + nl0 + j;
+        const int nc = min(n, N - 1);
+        const float t = thr[nc], sg = sgn[nc];
+#pragma unroll
+        for (int m = 0; m < MS; ++m) {
+            float v = acc[j][m];
+            for (int off = 32; off > 0; off >>= 1)
+                v += __shfl_xor(v, off, kWave);
+            if (lane == 0) {
+                decided[m][nl0 + j] = n < N && sg * v >= t;
+                if (pre && n < N && m < M)
+                    pre[(int64_t)m * N + n] = v;
+            }
+        }
+    }
+    __syncthreads();
+    for (int m = wave; m < M; m += WAVES) {
+        const uint64_t word = __ballot(lane < RB && decided[m][lane % RB] != 0);
+        if (lane != 0)
+            continue;
+        if (RB == 64)
+            bits[(int64_t)m * gridDim.x + blockIdx.x] = word;
+        else   // 16-bit piece blockIdx.x % 4 of word blockIdx.x / 4 (little-endian)
+            reinterpret_cast<uint16_t *>(bits)[(int64_t)m * gridDim.x + blockIdx.x] = (uint16_t)word;
+    }
+}
+
+// The same layer for up to 4 input rows with the weights bit-packed ([N][ceil(K/64)] words as
+// from esp_pack_f32, bit 1 = +1): a lane takes 8 consecutive k per step, i.e. one byte of each
+// of its wave's 4 weight rows and 8 inputs per row of X, and adds or subtracts each input
+// (x XOR sign bit, then add).  1/32 of the weight traffic of the float form, which is what a
+// network evaluated one image at a time spends its first layer on.
+template <int MS, bool VEC8, int WAVES>
+__global__ __launch_bounds__(WAVES * 64)
+void dense_f32_bw_gemv_bits_kernel(const float *__restrict__ X, const uint32_t *__restrict__ Wb,
+                                   const float *__restrict__ thr, const float *__restrict__ sgn,
+                                   uint64_t *__restrict__ bits, float *__restrict__ pre, int M, int N, int K)
+{
+    constexpr int NPW = 4;                       // neurons per wave
+    constexpr int RB = NPW * WAVES;              // neurons per block: 64 or 16
+    __shared__ unsigned char decided[MS][RB];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int n_blk = blockIdx.x * RB;
+    const int nl0 = wave * NPW;
+    const int row_dw = 2 * ((K + 63) / 64);
+    float acc[NPW][MS];
+#pragma unroll
+    for (int j = 0; j < NPW; ++j)
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+            acc[j][m] = 0.0f;
+    // rows beyond N read the last row: their results are never used
+    const uint32_t *wrow[NPW];
+#pragma unroll
+    for (int j = 0; j < NPW; ++j)
+        wrow[j] = Wb + (int64_t)min(n_blk + nl0 + j, N - 1) * row_dw;
+    for (int k = 8 * lane; k < K; k += 8 * kWave) {
+        uint32_t wbyte[NPW];
+#pragma unroll
+        for (int j = 0; j < NPW; ++j)
+            wbyte[j] = wrow[j][k / 32] >> (k % 32);      // bits k .. k+7 in the low byte
+#pragma unroll
+        for (int m = 0; m < MS; ++m) {
+            if (m >= M)
+                continue;
+            const float *xp = X + (int64_t)m * K + k;
+            float x[8];
+            if (VEC8) {                                   // K % 8 == 0: whole steps, 16-byte loads
+                const float4 lo = *reinterpret_cast<const float4 *>(xp);
+                const float4 hi = *reinterpret_cast<const float4 *>(xp + 4);
+                x[0] = lo.x, x[1] = lo.y, x[2] = lo.z, x[3] = lo.w;
+                x[4] = hi.x, x[5] = hi.y, x[6] = hi.z, x[7] = hi.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x[e] = k + e < K ? xp[e] : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < NPW; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    // bit 1: + x, bit 0: - x
+                    const uint32_t flipsign = (~(wbyte[j] >> e) & 1u) << 31;
+                    acc[j][m] += __uint_as_float(__float_as_uint(x[e]) ^ flipsign);
+                }
         }
     }
 #pragma unroll
@@ -745,12 +855,13 @@ namespace esp {
 // Tiled float dense layer: with bits != null the fused layer on the bf16 matrix cores (threshold
 // epilogue, Y optional), else the plain fp32 product.
 static int dense_mfma_launch(const float *X, const float *W, float *Y, const float *thr, const float *sgn,
-                             uint64_t *bits, int64_t M, int64_t N, int64_t K, hipStream_t s)
+                             uint64_t *bits, int64_t M, int64_t N, int64_t K, hipStream_t s,
+                             const uint64_t *Wbits = nullptr)
 {
     const int64_t gy = ceil_div(M, 64);
     if (gy > 65535)
         return ESP_ESHAPE;
-    const bool vec4 = K % 4 == 0 && aligned(X, 16) && aligned(W, 16);
+    const bool vec4 = K % 4 == 0 && aligned(X, 16) && (Wbits || aligned(W, 16));
     if (bits) {
         // the fused layer of a binary network (+-1 weights): the bf16 matrix cores, three exact
         // terms per input.  Measured on the MLP's first layer (N = 4096, K = 784) at 8 ... 256 /
@@ -763,12 +874,12 @@ static int dense_mfma_launch(const float *X, const float *W, float *Y, const flo
         const dim3 grid((unsigned)ceil_div(N, 64 * g), (unsigned)ceil_div(M, bm));
 #define ESP_DENSE_BF16(BMV, GV, V)                                                                         \
     do {                                                                                                   \
-        if (bits)                                                                                          \
-            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, true>), grid, dim3(256), 0, s, X, W, Y, thr, \
-                               sgn, bits, (int)M, (int)N, (int)K);                                         \
+        if (Wbits)                                                                                         \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, true, true>), grid, dim3(256), 0, s, X,    \
+                               static_cast<const void *>(Wbits), Y, thr, sgn, bits, (int)M, (int)N, (int)K); \
         else                                                                                               \
-            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, false>), grid, dim3(256), 0, s, X, W, Y, thr, \
-                               sgn, bits, (int)M, (int)N, (int)K);                                         \
+            hipLaunchKernelGGL((dense_bf16x3_kernel<BMV, GV, V, true, false>), grid, dim3(256), 0, s, X,   \
+                               static_cast<const void *>(W), Y, thr, sgn, bits, (int)M, (int)N, (int)K);   \
     } while (0)
         if (bm == 128 && vec4)
             ESP_DENSE_BF16(128, 2, true);
@@ -872,6 +983,51 @@ extern "C" int esp_dense_f32_bn_sign_pack(const float *X, const float *W, const 
     else
         ESP_GEMV_BITS_F32(4, false);
 #undef ESP_GEMV_BITS_F32
+    return launch_status();
+}
+
+extern "C" int esp_dense_f32_bw_bn_sign_pack(const float *X, const uint64_t *Wbits, const float *thr,
+                                             const float *sgn, uint64_t *bits, float *pre, int64_t M,
+                                             int64_t N, int64_t K, esp_stream stream)
+{
+    using namespace esp;
+    if (M < 0 || N <= 0 || K <= 0)
+        return ESP_EINVAL;
+    if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 30))
+        return ESP_ESHAPE;
+    if (M == 0)
+        return ESP_OK;
+    if (!X || !Wbits || !thr || !sgn || !bits)
+        return ESP_EINVAL;
+    if (!aligned(X, 4) || !aligned(Wbits, 8) || !aligned(thr, 4) || !aligned(sgn, 4) || !aligned(bits, 8) ||
+        (pre && !aligned(pre, 4)))
+        return ESP_EALIGN;
+    hipStream_t s = as_stream(stream);
+    if (M > 4)
+        return dense_mfma_launch(X, nullptr, pre, thr, sgn, bits, M, N, K, s, Wbits);
+    const bool vec8 = K % 8 == 0 && aligned(X, 16);
+    const int64_t Nw = ceil_div(N, 64);
+    const bool wide = Nw >= 256;
+    const dim3 grid((unsigned)(wide ? Nw : 4 * Nw));
+    const uint32_t *wb = reinterpret_cast<const uint32_t *>(Wbits);
+#define ESP_GEMV_BITS_BW(MS, V)                                                                            \
+    do {                                                                                                   \
+        if (wide)                                                                                          \
+            hipLaunchKernelGGL((dense_f32_bw_gemv_bits_kernel<MS, V, 16>), grid, dim3(1024), 0, s, X, wb,  \
+                               thr, sgn, bits, pre, (int)M, (int)N, (int)K);                               \
+        else                                                                                               \
+            hipLaunchKernelGGL((dense_f32_bw_gemv_bits_kernel<MS, V, 4>), grid, dim3(256), 0, s, X, wb,    \
+                               thr, sgn, bits, pre, (int)M, (int)N, (int)K);                               \
+    } while (0)
+    if (M == 1 && vec8)
+        ESP_GEMV_BITS_BW(1, true);
+    else if (M == 1)
+        ESP_GEMV_BITS_BW(1, false);
+    else if (vec8)
+        ESP_GEMV_BITS_BW(4, true);
+    else
+        ESP_GEMV_BITS_BW(4, false);
+#undef ESP_GEMV_BITS_BW
     return launch_status();
 }
 

@@ -46,7 +46,7 @@ class BinaryMLP:
 
     def __init__(self, layers, batch: int, eps: float, device="cuda", fused: bool = True,
                  first_layer: str = "float", engine: int = esp.ENGINE_XOR_POPCOUNT,
-                 keep_first_pre: bool = False):
+                 keep_first_pre: bool = False, packed_first_weights: bool = False):
         self.batch = batch
         self.keep_first_pre = keep_first_pre   # also write the first layer's float pre-activations
         self.engine = engine    # units that evaluate the fused binary layers (esp_engine)
@@ -55,8 +55,14 @@ class BinaryMLP:
         self.first_layer = first_layer
         self.fused = fused      # False: keep every int32 pre-activation (for layer-wise checks)
         self.sizes = [layers[0]["w"].shape[1]] + [l["w"].shape[0] for l in layers]
-        self.w1 = _dev_f32(layers[0]["w"], device)
         bitplane = first_layer == "bitplane"
+        # the float first layer's +-1 weights as floats (12.25 MiB for 4096 x 784) or bit-packed
+        # like every other layer's (0.4 MiB; Sec. 6.2 "Binary optimized layers"): same speed
+        self.packed_first_weights = packed_first_weights and not bitplane
+        if self.packed_first_weights:
+            self.w1, self.w1_bits = None, _pack_weights(layers[0]["w"], device)
+        else:
+            self.w1, self.w1_bits = _dev_f32(layers[0]["w"], device), None
         # the bit-plane layer as one matrix-core call (planes combined in the product's epilogue)
         # when the engine allows the matrix cores and the batch gives them enough tiles
         self.bitplane_fused = bitplane and fused and (
@@ -90,6 +96,9 @@ class BinaryMLP:
                       out=self.plane_dots.view(self.batch * 8, -1))
             esp.bitplane_combine(self.plane_dots, self.wsum0, out=self.pre[0])
             esp.bn_sign_pack(self.pre[0], self.bn[0].thr, self.bn[0].flip, out=self.act[0])
+        elif self.packed_first_weights:
+            esp.dense_f32_bw_bn_sign_pack(x, self.w1_bits, self.bn[0].thr, self.bn[0].sgn, out=self.act[0],
+                                          pre=self.pre[0] if self.keep_first_pre else None)
         else:
             # one kernel; the float pre-activations are written only when asked for
             esp.dense_f32_bn_sign_pack(x, self.w1, self.bn[0].thr, self.bn[0].sgn, out=self.act[0],

@@ -88,6 +88,10 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_bconv_workspace_bytes(2, 4, 4, 64, 7, 3, 1, 1) == 0
     assert lib.esp_bmaxpool(p, p, 1, 4, 4, 64, 5, 2, None) == -3        # pooled size 0
     assert lib.esp_bmaxpool(p, p, 1, 4, 4, 64, 2, 0, None) == -3
+    assert lib.esp_dense_f32_bw_bn_sign_pack(p, None, p, p, p, None, 1, 64, 64, None) == -1
+    assert lib.esp_dense_f32_bw_bn_sign_pack(p, p + 4, p, p, p, None, 1, 64, 64, None) == -2
+    assert lib.esp_dense_f32_bw_bn_sign_pack(p, p, p, p, p, None, 1, 64, 1 << 30, None) == -3
+    assert lib.esp_dense_f32_bw_bn_sign_pack(None, None, None, None, None, None, 0, 64, 64, None) == 0
     # sizes beyond what the kernels' 32-bit piece and tile indices hold are refused, not launched
     assert lib.esp_unroll(p, p, 65536, 64, 64, 128, 3, 3, 1, 1, None) == -3
     assert lib.esp_bmaxpool(p, p, 1 << 20, 64, 64, 128, 2, 2, None) == -3

@@ -80,6 +80,21 @@ def test_mlp_forward_fused_small_batch(batch):
 
 
 @pytest.mark.parametrize("batch", [1, 70])
+def test_mlp_forward_packed_first_layer_weights(batch):
+    # the float first layer reading its +-1 weights as bits: same tolerance band, later layers exact
+    layers = synth.mlp_params()
+    x = synth.mlp_input(batch)
+    net = nets.BinaryMLP(layers, batch, EPS, DEV, keep_first_pre=True, packed_first_weights=True)
+    assert net.w1 is None
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    ref = onets.mlp_forward(x, layers, EPS)
+    act0 = _check_first_layer(net.pre[0].cpu().numpy(), esp.packed_to_numpy(net.act[0]), ref[0],
+                              layers[0]["bn"], 4096)
+    ref = onets.mlp_forward(x, layers, EPS, first_act=act0)
+    assert np.array_equal(scores, ref[3]["pre"])
+
+
+@pytest.mark.parametrize("batch", [1, 70])
 def test_mlp_forward_bitplane_first_layer(batch):
     # 8-bit input, first layer by bit-planes (Eq. 3): integer everywhere, so the whole network
     # is bit-exact against the oracle with no tolerance band

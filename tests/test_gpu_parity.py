@@ -626,6 +626,27 @@ def test_dense_f32_bn_sign_pack(M, N, K):
     assert torch.equal(esp.dense_f32_bn_sign_pack(xd, wd, td, sd), bits)      # without `pre`
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 784), (2, 100, 50), (3, 64, 31), (4, 130, 784), (1, 65, 4),
+                                   (4, 1000, 1001), (5, 4096, 784), (70, 130, 97), (2, 16390, 64),
+                                   (64, 4096, 784), (1024, 4096, 784), (300, 70, 130), (65, 33, 36),
+                                   (257, 130, 97), (300, 200, 131), (1, 10, 1), (3, 70, 129)])
+def test_dense_f32_bw_bn_sign_pack(M, N, K):
+    # the same layer with its +-1 weights bit-packed
+    rng = np.random.default_rng(7 + M + 10 * N + 100 * K)
+    x = (rng.random((M, K), dtype=np.float32) - 0.25).astype(np.float32)
+    w = _pm1(rng, (N, K))
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K) + 0.25 * w.sum(axis=1)).astype(np.float32), bnp[3])
+    thr, sgn = esp.bn_fold_f32(*bnp, synth.BN_EPS)
+    xd, wb, td, sd = _f32(x), _packed_dev(w), _f32(thr), _f32(sgn)
+    pre = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    bits = esp.dense_f32_bw_bn_sign_pack(xd, wb, td, sd, pre=pre)
+    _assert_close_1e4(pre.cpu().numpy(), oracle.dense_f64(x, w))
+    want = oracle.pack_bits(oracle.bn_sign(pre.cpu().numpy().astype(np.float64), bnp, synth.BN_EPS))
+    assert np.array_equal(esp.packed_to_numpy(bits), want)
+    assert torch.equal(esp.dense_f32_bw_bn_sign_pack(xd, wb, td, sd), bits)      # without `pre`
+
+
 @pytest.mark.parametrize("M", [3, 70, 600])
 def test_dense_f32_bn_sign_pack_wide_dynamic_range(M):
     # signed inputs spread over six decades, exact zeros, values with all 24 significand bits set:
