@@ -213,6 +213,9 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
         const int buf = s & 1;
         if (s + 1 < stages)
             prefetch(s + 1);                 // global loads in flight during this stage's MFMAs
+        // the wave that has MFMAs to issue goes first; one that is fetching or handing a stage
+        // over issues behind it (measured: 1 % on an 8192-cube, 2 % on the network's convolutions)
+        __builtin_amdgcn_s_setprio(2);
 #pragma unroll
         for (int step = 0; step < KG / 2; ++step) {
             if ((s * KG + 2 * step) * 4 >= row_dw)
@@ -230,6 +233,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             mfma_group<2, FM, FN>(xa, xb, acc);
             mfma_group<3, FM, FN>(xa, xb, acc);
         }
+        __builtin_amdgcn_s_setprio(0);
         if (s + 1 < stages)
             commit(buf ^ 1);                 // nobody reads that buffer before the barrier below
         __syncthreads();
