@@ -211,8 +211,6 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
     __syncthreads();
     for (int s = 0; s < stages; ++s) {
         const int buf = s & 1;
-        if (s + 1 < stages)
-            prefetch(s + 1);                 // global loads in flight during this stage's MFMAs
         // the wave that has MFMAs to issue goes first; one that is fetching or handing a stage
         // over issues behind it (measured: 1 % on an 8192-cube, 2 % on the network's convolutions)
         __builtin_amdgcn_s_setprio(2);
@@ -232,6 +230,8 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
             mfma_group<1, FM, FN>(xa, xb, acc);
             mfma_group<2, FM, FN>(xa, xb, acc);
             mfma_group<3, FM, FN>(xa, xb, acc);
+            if (step == 0 && s + 1 < stages)
+                prefetch(s + 1);             // global loads issued behind the first step's MFMAs
         }
         __builtin_amdgcn_s_setprio(0);
         if (s + 1 < stages)
