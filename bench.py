@@ -41,7 +41,7 @@ VALU_PEAK_TBOPS = 64.0 / (1.0 / SIMPLE_RATE_OPS + 1.0 / FULL_RATE_OPS) / 1e12   
 # does not know about the faster xor): 1258.3 Tbop/s
 VALU_FULL_RATE_ONLY_TBOPS = 64.0 * FULL_RATE_OPS / 2 / 1e12
 HBM_PEAK_GBS = 8000.0
-BGEMM_8192_TRAFFIC_BYTES = int((2.0 * 36945 + 262144) * 1024)   # measured, see profiles/bgemm_8192_cube.txt
+BGEMM_8192_TRAFFIC_BYTES = int((2.0 * 36958 + 262144) * 1024)   # measured, see profiles/bgemm_8192_cube.txt
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 MFMA
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 MFMA_FP4_PEAK_TOPS = 10100.0   # dense fp4/fp6 MFMA, TFLOP/s; one binary MAC = 2 flop = 2 bop
@@ -185,7 +185,7 @@ def main() -> int:
                      # HBM bytes per launch from the committed counter runs of this command
                      # (profiles/bgemm_8192_cube.txt): 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
                      "traffic": BGEMM_8192_TRAFFIC_BYTES if n == 8192 else None,
-                     "traffic_detail": "read 2.0 x 36945 KiB + written 262144 KiB per launch (rocprofv3 --pmc "
+                     "traffic_detail": "read 2.0 x 36958 KiB + written 262144 KiB per launch (rocprofv3 --pmc "
                                        "FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy)" if n == 8192 else None,
                      # the same loop on registers only (esp_xor_popcount_probe): what instruction
                      # issue and the clock under this load allow; the peak assumes 2.4 GHz
