@@ -45,6 +45,17 @@ MUTATIONS = [
     ("bn_channel_index", "orc_bn_i32", "gamma[c], beta[c], mean[c], var[c]", "gamma[c], beta[c], mean[C - 1 - c], var[c]"),
     ("maxpool_is_min", "orc_maxpool_pm1", "int8_t best = -128;", "int8_t best = 127;\n#define ORC_MIN 1"),
     ("maxpool_window_column_ignored", "orc_maxpool_pm1", "n * stride + dx) * C + c]", "n * stride) * C + c]"),
+    # window != stride: each of these equals the right answer when win == stride, and with
+    # win >= stride (the pins' cases) none of them reads or writes outside its arrays
+    ("maxpool_stride_taken_as_window", "orc_maxpool_pm1", "const int64_t H2 = (H - win) / stride + 1;",
+     "stride = win;\n    const int64_t H2 = (H - win) / stride + 1;"),
+    ("maxpool_output_size_from_window", "orc_maxpool_pm1", "const int64_t H2 = (H - win) / stride + 1;",
+     "const int64_t H2 = (H - win) / win + 1;"),
+    ("maxpool_row_origin_steps_by_window", "orc_maxpool_pm1", "(b * H + m * stride + dy) * W", "(b * H + m * win + dy) * W"),
+    ("maxpool_column_origin_steps_by_window", "orc_maxpool_pm1", "W + n * stride + dx) * C + c]",
+     "W + n * win + dx) * C + c]"),
+    ("maxpool_window_extent_is_stride", "orc_maxpool_pm1", "for (int64_t dy = 0; dy < win; ++dy)",
+     "for (int64_t dy = 0; dy < stride; ++dy)"),
     ("dense_f64_reversed_weights", "orc_dense_f64", "(double)w[n * K + k]", "(double)w[n * K + (K - 1 - k)]"),
     ("dense_f64_single_precision_sum", "orc_dense_f64", "acc += (double)x[m * K + k] * (double)w[n * K + k];",
      "acc = (double)(float)(acc + (double)x[m * K + k] * (double)w[n * K + k]);"),
@@ -55,7 +66,15 @@ MUTATIONS = [
      "filt[((l2 * kh + (kh - 1 - dy)) * kw + (kw - 1 - dx)) * C + c]"),
 ]
 # the min-pool case also needs its comparison turned round
-_EXTRA = {"maxpool_is_min": ("if (v > best)", "if (v < best)")}
+_EXTRA = {"maxpool_is_min": ("if (v > best)", "if (v < best)"),
+          "maxpool_output_size_from_window": ("const int64_t W2 = (W - win) / stride + 1;",
+                                              "const int64_t W2 = (W - win) / win + 1;"),
+          # an origin that steps by the window stays inside the input only if the output size
+          # shrinks with it
+          "maxpool_row_origin_steps_by_window": ("const int64_t H2 = (H - win) / stride + 1;",
+                                                 "const int64_t H2 = (H - win) / win + 1;"),
+          "maxpool_column_origin_steps_by_window": ("const int64_t W2 = (W - win) / stride + 1;",
+                                                    "const int64_t W2 = (W - win) / win + 1;")}
 
 
 def _function_span(src, func):

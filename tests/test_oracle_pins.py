@@ -293,6 +293,41 @@ def test_maxpool_library_third_opinion_and_floor():
     assert np.array_equal(out, ref.permute(0, 2, 3, 1).numpy().astype(np.int8))
 
 
+@pytest.mark.parametrize("win,stride", [(3, 1), (3, 2), (3, 3), (2, 1), (4, 3)])
+def test_maxpool_window_differs_from_stride(win, stride):
+    # Pooling layer of Sec. 5.2 with a window that is not the stride: the window origin moves by
+    # `stride`, its extent is `win`, and the output size is floor((size - win) / stride) + 1.
+    # Brute force in numpy on a non-square input with odd sizes, then torch's max_pool2d as a
+    # third opinion.  A mistake that swaps the two parameters anywhere changes a value or the shape.
+    rng = np.random.default_rng(210 + 10 * win + stride)
+    x = _pm1(rng, (2, 9, 11, 3))
+    out = oracle.maxpool_pm1(x, win, stride)
+    H2, W2 = (9 - win) // stride + 1, (11 - win) // stride + 1
+    assert out.shape == (2, H2, W2, 3)
+    ref = np.empty((2, H2, W2, 3), dtype=np.int8)
+    for m in range(H2):
+        for n in range(W2):
+            ref[:, m, n, :] = x[:, m * stride:m * stride + win, n * stride:n * stride + win, :].max(axis=(1, 2))
+    assert np.array_equal(out, ref)
+    lib = torch.nn.functional.max_pool2d(torch.from_numpy(x.astype(np.float32)).permute(0, 3, 1, 2), win, stride)
+    assert np.array_equal(out, lib.permute(0, 2, 3, 1).numpy().astype(np.int8))
+
+
+def test_maxpool_single_plus_one_marks_exactly_the_windows_that_hold_it():
+    # One +1 in a field of -1: output (m, n) is +1 exactly when m*stride <= y < m*stride + win and
+    # n*stride <= x < n*stride + win (closed form, no library).
+    for win, stride, y, x in ((3, 1, 4, 5), (3, 2, 4, 6), (2, 1, 3, 7), (3, 3, 5, 2)):
+        a = -np.ones((1, 8, 10, 1), dtype=np.int8)
+        a[0, y, x, 0] = 1
+        out = oracle.maxpool_pm1(a, win, stride)
+        H2, W2 = (8 - win) // stride + 1, (10 - win) // stride + 1
+        assert out.shape == (1, H2, W2, 1)
+        for m in range(H2):
+            for n in range(W2):
+                inside = m * stride <= y < m * stride + win and n * stride <= x < n * stride + win
+                assert out[0, m, n, 0] == (1 if inside else -1), (win, stride, m, n)
+
+
 # ------------------------------------------------------------------ float first layer
 def test_float_dense_and_conv_against_library():
     rng = np.random.default_rng(22)
