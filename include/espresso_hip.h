@@ -364,14 +364,24 @@ int esp_bitplane_dense(const uint64_t *planes, const uint64_t *W, const int32_t 
 /* ------------------------------------------------------------------------- */
 /* Measurement aid: the in-register ceiling of the inner loop of Eq. 2 (Sec.  */
 /* 4.2, with XOR for XNOR).  Launches `blocks` blocks of 256 lanes; every lane */
-/* runs `iters` rounds of an 8 x 8 register block of v_xor_b32 + accumulating  */
-/* v_bcnt_u32_b32 pairs on values that stay in registers (no memory traffic    */
-/* besides one final store per lane).  sink (device, uint32 [blocks * 256])    */
-/* receives each lane's counter sum; *bop (HOST) receives the number of binary */
-/* operations of the launch (64 per pair), so that bop / time is comparable    */
-/* with esp_bgemm's 2*M*N*K / time.  blocks, iters in [1, 2^20].               */
+/* runs `iters` rounds of an 8 x 8 register block on values that stay in        */
+/* registers (no memory traffic besides one final store per lane).  mode:       */
+/*   ESP_PROBE_PAIR           v_xor_b32 + accumulating v_bcnt_u32_b32 pairs in  */
+/*                            the product kernel's instruction pattern; *work = */
+/*                            binary operations of the launch (64 per pair), so */
+/*                            work / time compares with esp_bgemm's 2*M*N*K / t */
+/*   ESP_PROBE_XOR_ONLY       two dependent v_xor_b32 per slot                  */
+/*   ESP_PROBE_POPCOUNT_ONLY  two dependent v_bcnt_u32_b32 per slot             */
+/*                            *work = lane instructions of the launch (64 lanes */
+/*                            per wave instruction): the rate each instruction  */
+/*                            sustains alone, from which the peak of the pair   */
+/*                            follows as 64 / (1/xor_rate + 1/popcount_rate).   */
+/* sink (device, uint32 [blocks * 256]) receives each lane's counter sum; work  */
+/* is HOST memory.  blocks, iters in [1, 2^20]; another mode: ESP_EINVAL.       */
 /* ------------------------------------------------------------------------- */
-int esp_xor_popcount_probe(uint32_t *sink, int blocks, int iters, int64_t *bop, esp_stream stream);
+enum esp_probe_mode { ESP_PROBE_PAIR = 0, ESP_PROBE_XOR_ONLY = 1, ESP_PROBE_POPCOUNT_ONLY = 2 };
+
+int esp_xor_popcount_probe(uint32_t *sink, int blocks, int iters, int mode, int64_t *work, esp_stream stream);
 
 #ifdef __cplusplus
 }

@@ -82,7 +82,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_bn_sign_pack_pool2.argtypes = [vp, vp, vp, vp, vp] + [i32] * 9 + [i32, vp]
         l.esp_dense_f32_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_dense_f32_bw_bn_sign_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
-        l.esp_xor_popcount_probe.argtypes = [vp, i32, i32, vp, vp]
+        l.esp_xor_popcount_probe.argtypes = [vp, i32, i32, i32, vp, vp]
         l.esp_bitplane_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp]
         l.esp_version.argtypes = []
         for name in EXPORTS:
@@ -520,15 +520,19 @@ def bitplane_dense(planes: torch.Tensor, w: torch.Tensor, wsum: torch.Tensor, k:
     return bits, y
 
 
-def xor_popcount_probe(sink: torch.Tensor, blocks: int, iters: int) -> int:
-    """``esp_xor_popcount_probe``: launch the in-register xor + popcount loop; returns the number
-    of binary operations the launch performs.  ``sink``: uint32/int32 [blocks * 256] on the device."""
+PROBE_PAIR, PROBE_XOR_ONLY, PROBE_POPCOUNT_ONLY = 0, 1, 2
+
+
+def xor_popcount_probe(sink: torch.Tensor, blocks: int, iters: int, mode: int = PROBE_PAIR) -> int:
+    """``esp_xor_popcount_probe``: launch the in-register xor + popcount loop (or one of the two
+    instructions alone); returns the work of the launch: binary operations for ``PROBE_PAIR``, lane
+    instructions for the other modes.  ``sink``: uint32/int32 [blocks * 256] on the device."""
     if sink.numel() < blocks * 256:
         raise ValueError("sink must hold blocks * 256 values")
-    bop = ctypes.c_int64(0)
-    _check(lib().esp_xor_popcount_probe(_dev(sink, torch.int32, "sink"), int(blocks), int(iters),
-                                        ctypes.addressof(bop), _stream()), "esp_xor_popcount_probe")
-    return int(bop.value)
+    work = ctypes.c_int64(0)
+    _check(lib().esp_xor_popcount_probe(_dev(sink, torch.int32, "sink"), int(blocks), int(iters), int(mode),
+                                        ctypes.addressof(work), _stream()), "esp_xor_popcount_probe")
+    return int(work.value)
 
 
 # ------------------------------------------------------------------ host <-> device helpers

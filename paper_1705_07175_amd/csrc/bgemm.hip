@@ -108,6 +108,7 @@ struct StoreSignBits {
     const int32_t *thr;     // [N]
     const uint64_t *flip;   // [Nw]
     int Nw;
+    int N;                  // columns; flip bits beyond them are ignored
     int pool_log2w;         // 0: no pooling; else log2 of the output width W2 of the convolution
 
     // mismatch-count threshold: dot = K - 2a >= thr  <=>  a <= floor((K - thr) / 2)
@@ -122,7 +123,7 @@ struct StoreSignBits {
     // final bits of a lane's word (0 beyond the last word of the row)
     __device__ __forceinline__ uint64_t finish(const LaneWord &lw, int w) const
     {
-        return (lw.have && w < Nw) ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flip[w]) : 0ull;
+        return (lw.have && w < Nw) ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ (flip[w] & valid_cols_mask(w, N))) : 0ull;
     }
 
     // 8 x 8 counters per lane: slots q = jg*8 + i, lo register = word jg 0, hi = word jg 1
@@ -327,7 +328,7 @@ void bgemm_tile_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const St
         for (int c = tid; c < BN; c += NT)
             lim_s[c] = bits.mismatch_limit(n0 + c, N, K_true);
         if (tid < BN / 64)
-            flip_s[tid] = (n0 >> 6) + tid < bits.Nw ? bits.flip[(n0 >> 6) + tid] : 0ull;
+            flip_s[tid] = (n0 >> 6) + tid < bits.Nw ? bits.flip[(n0 >> 6) + tid] & valid_cols_mask((n0 >> 6) + tid, N) : 0ull;
     }
 
     const int stages = (row_dw + kStageDw - 1) / kStageDw;
@@ -459,7 +460,7 @@ static int launch_tile2(const ASrc &asrc, const uint32_t *b, const TileOut &o, i
     const dim3 grid((unsigned)(per_xcd * kXcd));
     const dim3 block((BM / TM) * (BN / TN));
     const StoreDots dots{o.C, (N % 4 == 0) && aligned(o.C, 16)};
-    const StoreSignBits bits{o.bits, o.thr, o.flip, (int)ceil_div(N, 64), o.pool_log2w};
+    const StoreSignBits bits{o.bits, o.thr, o.flip, (int)ceil_div(N, 64), (int)N, o.pool_log2w};
     if (o.bits)
         hipLaunchKernelGGL((bgemm_tile_kernel<BM, BN, TM, TN, ASrc, VEC16B, true>), grid, block, 0, stream,
                            asrc, b, dots, bits, (int)M, (int)N, (int)K_true, (int)row_dw, tiles_m, tiles_n,
@@ -571,7 +572,7 @@ void bfew_bits_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const int
         const int t = min(max(thr[min(n, N - 1)], -K_true), K_true + 1);
         byte |= (n < N && a <= ((K_true - t) >> 1)) ? 1u << j : 0u;
     }
-    byte ^= (uint32_t)(flip[piece / 8] >> (8 * (piece % 8))) & 0xffu;
+    byte ^= (uint32_t)((flip[piece / 8] & valid_cols_mask(piece / 8, N)) >> (8 * (piece % 8))) & 0xffu;
     const int pieces = gridDim.y;            // bytes per packed output row
     const int r = m0 + lane;
     if (pool_log2w == 0) {
@@ -878,10 +879,10 @@ void bgemv_bits_kernel(const uint64_t *__restrict__ A, const uint64_t *__restric
         if (lane != 0)
             continue;
         if (RB == 64) {
-            out[(int64_t)m * gridDim.x + blockIdx.x] = word ^ flip[blockIdx.x];
+            out[(int64_t)m * gridDim.x + blockIdx.x] = word ^ (flip[blockIdx.x] & valid_cols_mask(blockIdx.x, N));
         } else {
             // quarter blockIdx.x % 4 of word blockIdx.x / 4 (little-endian: 16-bit piece j = bits 16 j ..)
-            const uint64_t fl = flip[blockIdx.x / 4] >> (16 * (blockIdx.x % 4));
+            const uint64_t fl = (flip[blockIdx.x / 4] & valid_cols_mask(blockIdx.x / 4, N)) >> (16 * (blockIdx.x % 4));
             reinterpret_cast<uint16_t *>(out)[(int64_t)m * gridDim.x + blockIdx.x] = (uint16_t)(word ^ fl);
         }
     }

@@ -192,7 +192,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const int wi = ((n0 + wn) >> 6) + w;
-            fl[w] = wi < o.Nw ? o.flip[wi] : 0ull;
+            fl[w] = wi < o.Nw ? o.flip[wi] & valid_cols_mask(wi, N) : 0ull;
         }
     }
 
@@ -386,7 +386,7 @@ void bgemm_mfma_kernel(const ASrc asrc, const uint32_t *__restrict__ B, const Mf
                         for (int w = 0; w < FN / 2; ++w) {
                             const int wi = ((n0 + wn) >> 6) + w;
                             if (wi < o.Nw)
-                                o.bits[img * o.Nw + wi] = (((uint64_t)m32[2 * w + 1] << 32) | m32[2 * w]) ^ o.flip[wi];
+                                o.bits[img * o.Nw + wi] = (((uint64_t)m32[2 * w + 1] << 32) | m32[2 * w]) ^ (o.flip[wi] & valid_cols_mask(wi, N));
                         }
                     }
                 }

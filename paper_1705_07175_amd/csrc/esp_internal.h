@@ -67,6 +67,15 @@ __device__ __forceinline__ uint32_t fd_div(uint32_t n, const FastDiv f)
     return f.div == 1 ? n : (__umulhi(n, f.mul) >> f.shift);
 }
 
+// Bits of 64-column word w that belong to real columns (n < N).  A caller's flip word may carry
+// set bits beyond N; they must not reach the packed output, whose tail bits are zero by the
+// packing convention (the next product relies on that).
+__host__ __device__ __forceinline__ uint64_t valid_cols_mask(int w, int N)
+{
+    const int left = N - w * 64;
+    return left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+}
+
 // Number of blocks for a grid-stride kernel.  Measured on MI355X, streaming kernels reach
 // their best HBM bandwidth when the grid covers the whole array with one item per thread
 // (blocks are dispatched in order, so the blocks in flight sweep memory as one front);

@@ -29,13 +29,14 @@ struct ThresholdI32 {
     using in_t = int32_t;
     const int32_t *thr;
     const uint64_t *flip;
+    int C;
     struct Lane { int32_t t; };
     __device__ __forceinline__ Lane lane_state(int c, bool in_range) const
     {
         return Lane{in_range ? thr[c] : 0};
     }
     __device__ __forceinline__ bool bit(int32_t x, const Lane &s) const { return x >= s.t; }
-    __device__ __forceinline__ uint64_t post(uint64_t word, int w) const { return word ^ flip[w]; }
+    __device__ __forceinline__ uint64_t post(uint64_t word, int w) const { return word ^ (flip[w] & valid_cols_mask(w, C)); }
 };
 
 struct ThresholdF32 {
@@ -201,7 +202,7 @@ extern "C" int esp_bn_sign_pack(const int32_t *x, const int32_t *thr, const uint
         return ESP_EINVAL;
     if (!aligned(x, 4) || !aligned(thr, 4) || !aligned(flip, 8) || !aligned(out, 8))
         return ESP_EALIGN;
-    return launch_rowbits<ThresholdI32>(x, out, rows, C, ThresholdI32{thr, flip}, as_stream(stream));
+    return launch_rowbits<ThresholdI32>(x, out, rows, C, ThresholdI32{thr, flip, C}, as_stream(stream));
 }
 
 extern "C" int esp_bn_sign_pack_f32(const float *x, const float *thr, const float *sgn,

@@ -15,6 +15,11 @@ constexpr int kProbeRows = 8, kProbeCols = 8;   // the register block of the til
 // compiler adds the one between consecutive asm statements).  The pairs are opaque to the
 // optimiser (it would otherwise hoist the loop-invariant XORs), and the 64 counters are summed
 // into `sink` so that the work is observable.
+//
+// MODE 1 and 2 issue the two instructions separately -- two dependent v_xor_b32, or two dependent
+// accumulating v_bcnt_u32_b32, per slot of the same 8 x 8 register block -- which gives the rate
+// each of them sustains alone: the two numbers from which the peak of the pair follows.
+template <int MODE>
 __global__ __launch_bounds__(kProbeThreads) void xor_popcount_probe_kernel(uint32_t *__restrict__ sink, int iters)
 {
     uint32_t a[kProbeRows], b[kProbeCols], acc[kProbeRows][kProbeCols];
@@ -31,6 +36,20 @@ __global__ __launch_bounds__(kProbeThreads) void xor_popcount_probe_kernel(uint3
         for (int i = 0; i < kProbeRows; ++i)
 #pragma unroll
             for (int j = 0; j < kProbeCols; j += 4) {
+                if (MODE == ESP_PROBE_XOR_ONLY) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        asm volatile("v_xor_b32 %0, %1, %0\n\tv_xor_b32 %0, %2, %0"
+                                     : "+v"(acc[i][j + c]) : "v"(a[i]), "v"(b[j + c]));
+                    continue;
+                }
+                if (MODE == ESP_PROBE_POPCOUNT_ONLY) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        asm volatile("v_bcnt_u32_b32 %0, %1, %0\n\tv_bcnt_u32_b32 %0, %2, %0"
+                                     : "+v"(acc[i][j + c]) : "v"(a[i]), "v"(b[j + c]));
+                    continue;
+                }
                 uint32_t t;
                 asm volatile("v_xor_b32 %0, %5, %6\n\tv_bcnt_u32_b32 %1, %0, %1\n\ts_nop 0\n\t"
                              "v_xor_b32 %0, %5, %7\n\tv_bcnt_u32_b32 %2, %0, %2\n\ts_nop 0\n\t"
@@ -49,16 +68,30 @@ __global__ __launch_bounds__(kProbeThreads) void xor_popcount_probe_kernel(uint3
 
 } // namespace esp
 
-extern "C" int esp_xor_popcount_probe(uint32_t *sink, int blocks, int iters, int64_t *bop, esp_stream stream)
+extern "C" int esp_xor_popcount_probe(uint32_t *sink, int blocks, int iters, int mode, int64_t *work,
+                                      esp_stream stream)
 {
     using namespace esp;
-    if (!sink || !bop || blocks <= 0 || iters <= 0)
+    if (!sink || !work || blocks <= 0 || iters <= 0)
+        return ESP_EINVAL;
+    if (mode != ESP_PROBE_PAIR && mode != ESP_PROBE_XOR_ONLY && mode != ESP_PROBE_POPCOUNT_ONLY)
         return ESP_EINVAL;
     if (blocks > (1 << 20) || iters > (1 << 20))
         return ESP_ESHAPE;
-    // one pair = 32 binary multiply-accumulates = 64 binary operations
-    *bop = (int64_t)blocks * kProbeThreads * iters * kProbeRows * kProbeCols * 64;
-    hipLaunchKernelGGL(xor_popcount_probe_kernel, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, sink,
-                       iters);
+    const int64_t slots = (int64_t)blocks * kProbeThreads * iters * kProbeRows * kProbeCols;
+    const dim3 grid(blocks), block(kProbeThreads);
+    if (mode == ESP_PROBE_PAIR) {
+        // one pair = 32 binary multiply-accumulates = 64 binary operations
+        *work = slots * 64;
+        hipLaunchKernelGGL(xor_popcount_probe_kernel<ESP_PROBE_PAIR>, grid, block, 0, (hipStream_t)stream, sink, iters);
+    } else if (mode == ESP_PROBE_XOR_ONLY) {
+        *work = slots * 2;       // lane instructions
+        hipLaunchKernelGGL(xor_popcount_probe_kernel<ESP_PROBE_XOR_ONLY>, grid, block, 0, (hipStream_t)stream, sink,
+                           iters);
+    } else {
+        *work = slots * 2;
+        hipLaunchKernelGGL(xor_popcount_probe_kernel<ESP_PROBE_POPCOUNT_ONLY>, grid, block, 0, (hipStream_t)stream,
+                           sink, iters);
+    }
     return launch_status();
 }

@@ -117,14 +117,15 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, None, p, None, 1, 4, 4, None) == -1
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p + 4, None, 1, 4, 4, None) == -2
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p, None, 0, 4, 4, None) == 0
-    assert lib.esp_xor_popcount_probe(p, 4, 4, None, None) == -1
+    assert lib.esp_xor_popcount_probe(p, 4, 4, 0, None, None) == -1
     assert lib.esp_bitplane_dense(p, p, p, None, None, None, None, 2, 64, 64, None) == -1
     assert lib.esp_bitplane_dense(p, p, p, None, None, p, None, 2, 64, 64, None) == -1
     assert lib.esp_bitplane_dense(p, p, p, p, p, p, p, 2, 64, 1 << 21, None) == -3
     assert lib.esp_bitplane_dense(p, p, p, p, p, p, p, 0, 64, 64, None) == 0
     assert lib.esp_bitplane_dense(p, p, p + 2, p, p, p, p, 2, 64, 64, None) == -2
-    assert lib.esp_xor_popcount_probe(p, 0, 4, p, None) == -1
-    assert lib.esp_xor_popcount_probe(p, 4, (1 << 20) + 1, p, None) == -3
+    assert lib.esp_xor_popcount_probe(p, 0, 4, 0, p, None) == -1
+    assert lib.esp_xor_popcount_probe(p, 4, 4, 3, p, None) == -1
+    assert lib.esp_xor_popcount_probe(p, 4, (1 << 20) + 1, 2, p, None) == -3
     # fused pool: shapes that cannot hold whole row pairs in a tile are refused up front
     assert lib.esp_bconv_pool2_fusable(32, 32, 128, 3, 3, 1, 1) == 1
     assert lib.esp_bconv_pool2_fusable(8, 8, 512, 3, 3, 1, 1) == 1

@@ -746,3 +746,15 @@ def test_xor_popcount_probe_counts_what_it_claims():
             x = ai ^ bj
             want += np.array([bin(int(v)).count("1") for v in x])
     assert np.array_equal(sink.cpu().numpy().astype(np.int64), want * iters)
+    # the single-instruction modes: two dependent xors per slot (acc ^= a; acc ^= b: after an odd
+    # number of rounds every counter holds a ^ b), two dependent popcount-accumulates per slot
+    assert esp.xor_popcount_probe(sink, blocks, iters, esp.PROBE_XOR_ONLY) == blocks * 256 * iters * 64 * 2
+    want_x = np.zeros(blocks * 256, dtype=np.uint64)
+    for ai in a:
+        for bj in b:
+            want_x = (want_x + (ai ^ bj)) & mask
+    assert np.array_equal(sink.cpu().numpy().view(np.uint32).astype(np.uint64), want_x)
+    assert esp.xor_popcount_probe(sink, blocks, iters, esp.PROBE_POPCOUNT_ONLY) == blocks * 256 * iters * 64 * 2
+    popc = lambda v: np.array([bin(int(t)).count("1") for t in v])
+    want_p = 8 * (sum(popc(ai) for ai in a) + sum(popc(bj) for bj in b))
+    assert np.array_equal(sink.cpu().numpy().astype(np.int64), want_p * iters)
