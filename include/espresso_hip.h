@@ -147,6 +147,31 @@ int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
               void *workspace, size_t workspace_bytes, esp_stream stream);
 
 /* ------------------------------------------------------------------------- */
+/* bconv_noalloc: esp_bconv for callers that cannot allocate device memory    */
+/* (code under HIP graph capture, tight serving loops, harnesses that forbid  */
+/* hipMalloc) and therefore cannot bring a workspace.  Same arguments without */
+/* the workspace, same results.  The lowered matrix of the general path (C    */
+/* not a multiple of 128, or in / filt not 16-byte aligned) is written to a   */
+/* fixed scratch array inside the library, ESP_BCONV_NOALLOC_MAX_BYTES =      */
+/* 16 MiB per GPU, held from library load until the process ends; a shape     */
+/* whose esp_bconv_workspace_bytes(...) exceeds it returns ESP_EWORKSPACE and */
+/* enqueues nothing.  The call allocates and frees nothing and does not       */
+/* synchronise.  The first call on a device looks up that device's copy of    */
+/* the array (a runtime query, no allocation): make it once outside a graph   */
+/* capture.  All calls on one GPU share the array: two calls may overlap only */
+/* if they are ordered on one stream (or otherwise serialised); calls on      */
+/* different streams of the same GPU race on it.  Nothing in the array needs  */
+/* clearing between calls: every word the product reads is written by the     */
+/* same call first.  Errors otherwise as esp_bconv (ESP_ELAUNCH if the        */
+/* device's array cannot be found).                                           */
+/* ------------------------------------------------------------------------- */
+#define ESP_BCONV_NOALLOC_MAX_BYTES ((size_t)16 << 20)
+
+int esp_bconv_noalloc(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                      int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                      esp_stream stream);
+
+/* ------------------------------------------------------------------------- */
 /* bn_fold (HOST function, run once per layer at load time): folds inference  */
 /* batch-norm followed by sign (Sec. 5.2 lists the batch-norm layer; Eq. 1)   */
 /* into one integer threshold per channel.  With                              */

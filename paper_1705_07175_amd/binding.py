@@ -30,7 +30,7 @@ EXPORTS = (
     "esp_bconv_bn_sign_pack", "esp_pad_correction", "esp_add_pad_correction",
     "esp_bitplane_pack_u8", "esp_row_sums", "esp_bitplane_combine", "esp_bgemm_mfma", "esp_bconv_mfma",
     "esp_bconv_pool2_fusable", "esp_bconv_bn_sign_pack_pool2", "esp_dense_f32_bn_sign_pack",
-    "esp_xor_popcount_probe", "esp_bitplane_dense", "esp_dense_f32_bw_bn_sign_pack",
+    "esp_xor_popcount_probe", "esp_bitplane_dense", "esp_dense_f32_bw_bn_sign_pack", "esp_bconv_noalloc",
 )
 
 _lib = None
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         l.esp_bconv_workspace_bytes.restype = ctypes.c_size_t
         l.esp_bconv_workspace_bytes.argtypes = [i32] * 8
         l.esp_bconv.argtypes = [vp, vp, vp] + [i32] * 9 + [vp, ctypes.c_size_t, vp]
+        l.esp_bconv_noalloc.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
         l.esp_bn_fold.argtypes = [vp, vp, vp, vp, f32, i32, vp, vp]
         l.esp_bn_sign_pack.argtypes = [vp, vp, vp, vp, i64, i32, vp]
         l.esp_bmaxpool.argtypes = [vp, vp] + [i32] * 6 + [vp]
@@ -218,6 +219,26 @@ def bconv(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
     _check(fn(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
               _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
            "esp_bconv_mfma" if engine == ENGINE_MFMA else "esp_bconv")
+    return out
+
+
+BCONV_NOALLOC_MAX_BYTES = 16 << 20
+
+
+def bconv_noalloc(x: torch.Tensor, filt: torch.Tensor, c: int, stride: int, pad: int,
+                  out: torch.Tensor) -> torch.Tensor:
+    """``esp_bconv_noalloc``: :func:`bconv` without a workspace (the lowered matrix goes to the
+    library's fixed scratch array).  ``out`` is required: nothing is allocated on this path."""
+    px, pf = _dev(x, PACKED, "x"), _dev(filt, PACKED, "filt")
+    B, H, W, Cw = x.shape
+    L2, kh, kw, Cw2 = filt.shape
+    if Cw != words(c) or Cw2 != Cw:
+        raise ValueError("channel words mismatch")
+    H2, W2 = conv_out(H, kh, stride, pad), conv_out(W, kw, stride, pad)
+    if out is None or out.numel() != B * max(H2, 0) * max(W2, 0) * L2:
+        raise ValueError("out must be the caller's int32 [B][H2][W2][L2] buffer")
+    _check(lib().esp_bconv_noalloc(px, pf, _dev(out, torch.int32, "out"), B, H, W, int(c), L2, kh, kw, stride, pad,
+                                   _stream()), "esp_bconv_noalloc")
     return out
 
 

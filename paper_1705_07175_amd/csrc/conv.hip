@@ -5,6 +5,8 @@
 // Because tensors are packed along channels (Sec. 5.1), every tap of a sliding volume is
 // a contiguous run of Cw words of the input pixel, so unrolling is a gather of whole
 // words: no bit moves.  Taps outside the image become zero words (= -1).
+#include <mutex>
+
 #include "esp_internal.h"
 
 namespace esp {
@@ -249,6 +251,62 @@ extern "C" int esp_bconv(const uint64_t *in, const uint64_t *filt, int32_t *out,
         return ESP_EINVAL;
     return esp::bconv_any(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw, stride, pad,
                           workspace, workspace_bytes, ESP_ENGINE_XOR_POPCOUNT, esp::as_stream(stream));
+}
+
+// ---- esp_bconv for callers that cannot allocate -------------------------------------
+// The lowered matrix of esp_bconv's general path lives in `scratch`, a fixed array in the
+// code object: each GPU that loads the library holds its own copy until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address it
+// returns for the current device is what the kernels get.
+constexpr size_t kScratchBytes = ESP_BCONV_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace esp {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void *g_scratch_ptr[kMaxDevices];      // per device: where that GPU's copy of `scratch` lies
+
+// Address of the current device's `scratch`, looked up once per device.
+static int scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return ESP_ELAUNCH;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return ESP_ELAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return ESP_OK;
+}
+
+} // namespace esp
+
+extern "C" int esp_bconv_noalloc(const uint64_t *in, const uint64_t *filt, int32_t *out,
+                                 int B, int H, int W, int C, int L2, int kh, int kw, int stride, int pad,
+                                 esp_stream stream)
+{
+    using namespace esp;
+    if (B > 0 && !out)
+        return ESP_EINVAL;
+    // shapes are judged before the scratch is looked up, so that argument errors come back the
+    // same way as from esp_bconv
+    const size_t need = esp_bconv_workspace_bytes(B, H, W, C, kh, kw, stride, pad);
+    const bool lowered = B > 0 && need > 0 && in && filt && !bconv_implicit_ok(in, filt, C);
+    if (lowered && need > kScratchBytes)
+        return ESP_EWORKSPACE;
+    void *ws = nullptr;
+    if (lowered) {
+        const int st = scratch_of_current_device(&ws);
+        if (st != ESP_OK)
+            return st;
+    }
+    return bconv_any(in, filt, out, nullptr, nullptr, nullptr, B, H, W, C, L2, kh, kw, stride, pad, ws,
+                     ws ? kScratchBytes : 0, ESP_ENGINE_XOR_POPCOUNT, as_stream(stream));
 }
 
 extern "C" int esp_bconv_mfma(const uint64_t *in, const uint64_t *filt, int32_t *out,

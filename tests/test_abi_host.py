@@ -118,6 +118,13 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p + 4, None, 1, 4, 4, None) == -2
     assert lib.esp_dense_f32_bn_sign_pack(p, p, p, p, p, None, 0, 4, 4, None) == 0
     assert lib.esp_xor_popcount_probe(p, 4, 4, 0, None, None) == -1
+    # the convolution that brings its own scratch: argument errors as esp_bconv, no GPU call is reached
+    assert lib.esp_bconv_noalloc(p, p, None, 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == -1
+    assert lib.esp_bconv_noalloc(None, p, p, 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == -1
+    assert lib.esp_bconv_noalloc(p, p, p, 1, 4, 4, 64, 8, 7, 3, 1, 1, None) == -3
+    assert lib.esp_bconv_noalloc(p, p, p, 1, 4, 4, 64, 8, 3, 3, 0, 1, None) == -3
+    assert lib.esp_bconv_noalloc(p, p, p, 0, 4, 4, 64, 8, 3, 3, 1, 1, None) == 0
+    assert lib.esp_bconv_noalloc(p, p, p, 256, 32, 32, 64, 8, 3, 3, 1, 1, None) == -4      # 18 MiB > 16 MiB
     assert lib.esp_bitplane_dense(p, p, p, None, None, None, None, 2, 64, 64, None) == -1
     assert lib.esp_bitplane_dense(p, p, p, None, None, p, None, 2, 64, 64, None) == -1
     assert lib.esp_bitplane_dense(p, p, p, p, p, p, p, 2, 64, 1 << 21, None) == -3
