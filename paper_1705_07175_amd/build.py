@@ -24,6 +24,7 @@ SOURCES = (
     ("bgemm_mfma.hip", ()),
     ("pack.hip", ()),
     ("conv.hip", ()),
+    ("bconv_patch.hip", ()),
     ("float_layers.hip", ()),
     ("bitplane.hip", ()),
     ("probe.hip", ()),

@@ -1,0 +1,439 @@
+// Binary convolution with the filters resident in LDS and the input streamed as image
+// patches (arXiv 1705.07175, Sec. 5.2 "Convolutional layers", Fig. 3; product of Eq. 2).
+//
+// The lowered matrix of Fig. 3 repeats every input pixel kh * kw times.  The general tile
+// kernel gathers those copies into LDS stage by stage; here a block tile of 128 consecutive
+// output pixels (whole image rows) keeps its input PATCH -- the rows it covers plus the
+// (kh - 1) x (kw - 1) halo, border pixels as zero words (= -1) -- in LDS once, and a lane
+// reads the operand of output pixel x at tap (dy, dx) from patch pixel (y + dy, x + dx).
+// A lane owns 8 consecutive pixels of one image row, so its eight operands of a k-group are
+// one LDS address plus immediates, and that address advances by one 16-byte chunk per
+// k-group (by the row pitch when dy changes).  A 3 x 3 layer's K is short (1152 - 4608 bits):
+// the block's 64 filters stay in LDS for all of it, and the block walks several row tiles,
+// fetching the next patch (1 - 4 chunks per thread) while it counts the current one, so that
+// after the first tile nothing waits for memory.  Per tile: one barrier.
+//
+// Used for stride-1 convolutions on 128, 256 or 512 channels whose output width is a power
+// of two between 8 and 128 (the layers of the Sec. 6.3 network); everything else takes the
+// gathering tile kernel.  Same results: int32 dots, or threshold + sign (+ 2x2 OR pool).
+#include <type_traits>
+
+#include "esp_internal.h"
+#include "tile_sources.h"
+#include "tile_epilogues.h"
+
+namespace esp {
+
+constexpr int kPBM = 128, kPBN = 64;       // block tile: output pixels x filters
+constexpr int kPTM = 8, kPTN = 4;          // counters per lane
+constexpr int kPTX = kPBN / kPTN, kPTY = kPBM / kPTM, kPNT = kPTX * kPTY;   // 16 x 16 lanes
+constexpr int kPatchMaxChunksPerThread = 4;   // a patch is at most 4 * 256 chunks of 16 bytes
+constexpr int kPatchMaxKG = 36;            // k-groups (128 bits each) of a filter: 3 x 3 x 512 channels
+constexpr int kPatchBBatch = kPatchMaxKG / 4;   // filter chunks per thread, all in flight at once
+constexpr int kPatchBPitch = kPBN + 1;     // chunks per k-group of the filter slab (+1: bank skew)
+constexpr int kPatchSlots = 2 * 256;       // blocks of a launch: two per compute unit
+
+struct PatchGeom {
+    const uint32_t *in;      // packed NHWC input
+    int B, H, W, pad;
+    int M;                   // output pixels B * H2 * W2
+    int log2w;               // W2 = 1 << log2w
+    int log2pix;             // log2 of the output pixels of one image inside a tile
+    int nimg;                // images per tile (1 when a tile lies inside one image)
+    int rows_img;            // output rows of one image inside a tile
+    int prow, pcol;          // patch rows per image, pixels per patch row
+    int pitch;               // chunks per patch row in LDS
+    int patch_chunks;        // chunks to fetch per tile: nimg * prow * pcol * CPP
+    int patch_lds_chunks;    // nimg * prow * pitch
+    int kwc;                 // k-groups per filter row: kw * CPP
+    int KG;                  // k-groups per filter: kh * kw * CPP
+    int cdw;                 // dwords per input pixel
+    FastDiv d_pcol, d_prow, d_tpi;         // divisions by pcol, prow, tiles per image
+};
+
+template <int CPP, int PCH, bool BITS>
+__global__ __launch_bounds__(kPNT, 3)
+void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, const StoreDots dots,
+                        const StoreSignBits bits, int N, int K_true, int tiles_m, int tiles_n, int G)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint4 *Bs = reinterpret_cast<uint4 *>(smem_raw);                     // [KG][kPatchBPitch]
+    uint4 *P0 = Bs + g.KG * kPatchBPitch;                                // two patch buffers
+    uint4 *P1 = P0 + g.patch_lds_chunks;
+    uint64_t *wt = reinterpret_cast<uint64_t *>(P1 + g.patch_lds_chunks);  // [kPBM] words for the pooled epilogue
+    uint64_t *flip_s = wt + kPBM;                                        // the block's flip word
+    int *lim_s = reinterpret_cast<int *>(flip_s + 2);                    // [kPBN] mismatch limits (16-byte aligned)
+
+    const int tid = threadIdx.x;
+    const int tx = tid % kPTX;
+    const int tyl = tid / kPTX;
+    // the four lane rows of a wave take pixel groups 32 tile rows apart, so that their operand
+    // reads fall into different LDS banks
+    const int ty = (tyl % 4) * 4 + tyl / 4;
+    const int tn = blockIdx.x % tiles_n;
+    const int first = blockIdx.x / tiles_n;      // this block walks row tiles first, first + G, ...
+    const int n0 = tn * kPBN;
+    if (first >= tiles_m)
+        return;
+
+    // ---- the block's filters: all K of 64 rows, fetched once.  Four threads share a row and take
+    // every fourth k-group of it, all of its loads in flight at once; column nl is register column
+    // nl % 4 of lane nl / 4 -------------------------------------------------------------------
+    {
+        const int nl = tid >> 2, kq = tid & 3;
+        const uint32_t *brow = filt + (int64_t)min(n0 + nl, N - 1) * (g.KG * 4);
+        uint4 *bdst = Bs + (nl % 4) * kPTX + nl / 4;
+        for (int kg = kq; kg < g.KG; kg += 4 * kPatchBBatch) {
+            uint4 bv[kPatchBBatch];
+#pragma unroll
+            for (int u = 0; u < kPatchBBatch; ++u)
+                bv[u] = *reinterpret_cast<const uint4 *>(brow + min(kg + 4 * u, g.KG - 1) * 4);
+#pragma unroll
+            for (int u = 0; u < kPatchBBatch; ++u)
+                if (kg + 4 * u < g.KG)
+                    bdst[(kg + 4 * u) * kPatchBPitch] = bv[u];
+        }
+    }
+
+    // ---- patch fetch: chunk q of the patch <-> (image, patch row, patch pixel, part) -----
+    uint4 pp[PCH];                                // PCH * 256 chunks cover the patch
+    uint32_t pkeep = 0;
+    auto prefetch = [&](int tm) {
+        uint32_t b0, y0;                         // first image and first output row of the tile (uniform)
+        if (g.nimg == 1) {
+            b0 = fd_div((uint32_t)tm, g.d_tpi);
+            y0 = ((uint32_t)tm - b0 * g.d_tpi.div) * g.rows_img;
+        } else {
+            b0 = (uint32_t)tm * g.nimg;
+            y0 = 0;
+        }
+        pkeep = 0;
+#pragma unroll
+        for (int i = 0; i < PCH; ++i) {
+            const uint32_t q = tid + i * kPNT;
+            const uint32_t qq = min(q, (uint32_t)g.patch_chunks - 1);
+            const uint32_t pix = qq / CPP, part = qq % CPP;
+            const uint32_t t = fd_div(pix, g.d_pcol), px = pix - t * g.pcol;
+            const uint32_t il = fd_div(t, g.d_prow), py = t - il * g.prow;
+            const int y = (int)(y0 + py) - g.pad, x = (int)px - g.pad;
+            const uint32_t b = b0 + il;
+            const bool inside = q < (uint32_t)g.patch_chunks && b < (uint32_t)g.B &&
+                                (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
+            // pixels outside the image read the first chunk of the input and are masked at the commit
+            const uint32_t off = inside ? ((b * g.H + y) * g.W + x) * g.cdw + part * 4 : 0u;
+            pp[i] = *reinterpret_cast<const uint4 *>(g.in + off);
+            pkeep |= inside ? 1u << i : 0u;
+        }
+    };
+    auto commit = [&](uint4 *P) {
+#pragma unroll
+        for (int i = 0; i < PCH; ++i) {
+            const uint32_t q = tid + i * kPNT;
+            if (q < (uint32_t)g.patch_chunks) {
+                const uint32_t pix = q / CPP, part = q % CPP;
+                const uint32_t t = fd_div(pix, g.d_pcol), px = pix - t * g.pcol;   // t = image * prow + patch row
+                P[t * g.pitch + px * CPP + part] = keep4(pp[i], (pkeep >> i) & 1u);
+            }
+        }
+    };
+    prefetch(first);
+
+    // thresholds and flip word of the block's 64 columns: the same for every tile, parked in LDS
+    // (the main loop needs the registers)
+    if constexpr (BITS) {
+        if (tid < kPBN)
+            lim_s[tid] = bits.mismatch_limit(n0 + tid, N, K_true);
+        if (tid == 0)
+            *flip_s = tn < bits.Nw ? bits.flip[tn] & valid_cols_mask(tn, N) : 0ull;
+    }
+    commit(P0);
+    __syncthreads();
+
+    // the lane's eight pixels: tile rows 8 ty .. 8 ty + 7 = one image row, x0 .. x0 + 7
+    const int r0 = 8 * ty;
+    const int il = r0 >> g.log2pix;
+    const int rem = r0 & ((1 << g.log2pix) - 1);
+    const int abase = (il * g.prow + (rem >> g.log2w)) * g.pitch + (rem & ((1 << g.log2w) - 1)) * CPP;
+    const int wrap = g.pitch - g.kwc;            // extra chunks to the next patch row when dy advances
+
+    int t = 0;
+    for (int tm = first; tm < tiles_m; tm += G, ++t) {
+        const uint4 *P = (t & 1) ? P1 : P0;
+        uint4 *Pn = (t & 1) ? P0 : P1;
+        // The next patch is fetched and committed on every trip, also on the last one (where it is
+        // the last tile again and never read): with both under a condition the compiler cannot
+        // see that a fetch is always followed by its commit, and makes the next trip's fetch wait
+        // for everything outstanding -- this trip's stores included.
+        prefetch(min(tm + G, tiles_m - 1));
+
+        int acc[kPTM][kPTN];
+
+        // One k-group: operands that arrived during the previous k-group are counted while those
+        // of the next one travel from LDS (two register sets alternate), as in the tile kernel.
+        // The first k-group of a tile sets the counters instead of adding to them.
+        auto kgroup = [&](auto first, const uint4 *pa, const uint4 *pa_next, const uint4 *pb_next, const uint4 &a0,
+                          const uint4 (&b)[kPTN], uint4 &a0_next, uint4 (&b_next)[kPTN]) {
+            constexpr bool kFirst = decltype(first)::value;
+            uint4 a[kPTM];
+            a[0] = a0;
+#pragma unroll
+            for (int i = 1; i < kPTM; ++i)
+                a[i] = pa[i * CPP];
+            a0_next = pa_next[0];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < kPTN; ++j) {
+                if constexpr (kFirst)
+                    xor_popc_set4(acc[0][j], a[0], b[j]);
+                else
+                    xor_popc_acc4(acc[0][j], a[0], b[j]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < kPTN; ++j)
+                b_next[j] = pb_next[j * kPTX];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 1; i < kPTM; ++i)
+#pragma unroll
+                for (int j = 0; j < kPTN; ++j) {
+                    if constexpr (kFirst)
+                        xor_popc_set4(acc[i][j], a[i], b[j]);
+                    else
+                        xor_popc_acc4(acc[i][j], a[i], b[j]);
+                }
+        };
+        // chunks from k-group k to k + 1 in the patch: 1, plus the row wrap after the last tap of a filter row
+        int u = 0;
+        auto advance = [&]() {
+            const int step = (u + 1 == g.kwc) ? 1 + wrap : 1;
+            u = (u + 1 == g.kwc) ? 0 : u + 1;
+            return step;
+        };
+        const uint4 *pa = P + abase;
+        const uint4 *pb = Bs + tx;
+        uint4 a0_even, b_even[kPTN], a0_odd, b_odd[kPTN];
+        a0_even = pa[0];
+#pragma unroll
+        for (int j = 0; j < kPTN; ++j)
+            b_even[j] = pb[j * kPTX];
+        // k-group 0 (and 1, if there is one) ahead of the loop, then pairs
+        int k = 0;
+        if (g.KG >= 2) {
+            const uint4 *pa1 = pa + advance();
+            const uint4 *pb1 = pb + kPatchBPitch;
+            kgroup(std::true_type{}, pa, pa1, pb1, a0_even, b_even, a0_odd, b_odd);
+            const bool last = 2 >= g.KG;
+            const int s2 = advance();
+            const uint4 *pa2 = last ? pa1 : pa1 + s2;
+            const uint4 *pb2 = last ? pb1 : pb1 + kPatchBPitch;
+            kgroup(std::false_type{}, pa1, pa2, pb2, a0_odd, b_odd, a0_even, b_even);
+            pa = pa2;
+            pb = pb2;
+            k = 2;
+        } else {
+            kgroup(std::true_type{}, pa, pa, pb, a0_even, b_even, a0_odd, b_odd);
+            k = 1;
+        }
+        for (; k + 1 < g.KG; k += 2) {
+            const uint4 *pa1 = pa + advance();
+            const uint4 *pb1 = pb + kPatchBPitch;
+            kgroup(std::false_type{}, pa, pa1, pb1, a0_even, b_even, a0_odd, b_odd);
+            const bool last = k + 2 >= g.KG;     // no k-group behind the pair: re-read the same chunks
+            const int s2 = advance();
+            const uint4 *pa2 = last ? pa1 : pa1 + s2;
+            const uint4 *pb2 = last ? pb1 : pb1 + kPatchBPitch;
+            kgroup(std::false_type{}, pa1, pa2, pb2, a0_odd, b_odd, a0_even, b_even);
+            pa = pa2;
+            pb = pb2;
+        }
+        if (k < g.KG)
+            kgroup(std::false_type{}, pa, pa, pb, a0_even, b_even, a0_odd, b_odd);
+
+        // The next patch goes to LDS before this tile's results are stored: loads and stores
+        // complete in order, so waiting for the patch behind the stores would wait for them too.
+        commit(Pn);
+
+        // ---- epilogue -----------------------------------------------------------------
+        const int m0 = tm * kPBM;
+        if constexpr (BITS) {
+            const int4 l4 = *reinterpret_cast<const int4 *>(&lim_s[tx * 4]);
+            const int lim[kPTN] = {l4.x, l4.y, l4.z, l4.w};
+            const uint64_t flipw = *flip_s;
+            LaneWord lw = bits.template tile_8x4<kPTY>(acc, lim, tx, ty);
+            lw.rl = r0 + (tx & 7);               // lane tx < 8 holds the word of the lane row's pixel tx
+            const uint64_t word = lw.have ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flipw) : 0ull;
+            if (bits.pool_log2w == 0) {
+                if (lw.have && m0 + lw.rl < g.M && tn < bits.Nw)
+                    bits.out[(int64_t)(m0 + lw.rl) * bits.Nw + tn] = word;
+            } else {
+                // 2x2 max-pool of +-1 values = OR of the sign bits of the tile's row pairs
+                if (lw.have)
+                    wt[lw.rl] = word;
+                __syncthreads();
+                pool_tile_store<kPBM, 1, kPNT>(wt, bits.out, m0, n0, g.M, bits.Nw, bits.pool_log2w, tid);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPTM; ++i) {
+                const int r = m0 + r0 + i;
+                if (r < g.M)
+                    dots.template row<kPTN, kPTX>(r, N, K_true, n0, tx, acc[i]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Geometry of the patch path for a shape, or false if the shape does not qualify.
+static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int kh, int kw, int stride, int pad,
+                            int H2, int W2, PatchGeom *g, size_t *lds_bytes)
+{
+    if (stride != 1 || C % 128 != 0)
+        return false;
+    const int cpp = C / 128;
+    if (cpp != 1 && cpp != 2 && cpp != 4)
+        return false;
+    if (W2 < 8 || W2 > 128 || (W2 & (W2 - 1)) != 0 || H2 < 1)
+        return false;
+    const int64_t pix_img = (int64_t)H2 * W2;
+    int nimg, rows_img;
+    int64_t tiles_per_img;
+    if (pix_img % kPBM == 0) {
+        nimg = 1;
+        rows_img = kPBM / W2;
+        tiles_per_img = pix_img / kPBM;
+    } else if (kPBM % pix_img == 0) {
+        nimg = (int)(kPBM / pix_img);
+        rows_img = H2;
+        tiles_per_img = 1;
+    } else {
+        return false;
+    }
+    const int64_t KG = (int64_t)kh * kw * cpp;
+    if (KG > kPatchMaxKG)
+        return false;
+    const int prow = rows_img + kh - 1, pcol = W2 + kw - 1;
+    const int64_t patch_chunks = (int64_t)nimg * prow * pcol * cpp;
+    if (patch_chunks > kPatchMaxChunksPerThread * kPNT)
+        return false;
+    const int pitch = pcol * cpp + 1;
+    const int64_t patch_lds = (int64_t)nimg * prow * pitch;
+    const size_t lds = (size_t)(KG * kPatchBPitch + 2 * patch_lds) * 16 + kPBM * 8 + 16 + kPBN * 4;
+    if (lds > 64 * 1024)
+        return false;
+    const int cdw = 2 * (C / 64);
+    if ((int64_t)B * H * W * cdw >= (1ll << 31) || (int64_t)B * pix_img >= (1ll << 31) || tiles_per_img >= (1ll << 30))
+        return false;
+    auto log2i = [](int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; };
+    g->in = reinterpret_cast<const uint32_t *>(in);
+    g->B = B;
+    g->H = H;
+    g->W = W;
+    g->pad = pad;
+    g->M = (int)(B * pix_img);
+    g->log2w = log2i(W2);
+    g->log2pix = log2i(nimg == 1 ? kPBM : pix_img);
+    g->nimg = nimg;
+    g->rows_img = rows_img;
+    g->prow = prow;
+    g->pcol = pcol;
+    g->pitch = pitch;
+    g->patch_chunks = (int)patch_chunks;
+    g->patch_lds_chunks = (int)patch_lds;
+    g->kwc = kw * cpp;
+    g->KG = (int)KG;
+    g->cdw = cdw;
+    g->d_pcol = make_fastdiv((uint32_t)pcol);
+    g->d_prow = make_fastdiv((uint32_t)prow);
+    g->d_tpi = make_fastdiv((uint32_t)tiles_per_img);
+    *lds_bytes = lds;
+    return true;
+}
+
+// Row tiles per block and blocks per filter tile for tiles_m x tiles_n tiles: the grid should be two
+// blocks per compute unit (two waves per SIMD keep the vector ALUs busy), each walking the same
+// number of row tiles.
+static void patch_grid(int64_t tiles_m, int64_t tiles_n, int64_t *G, int64_t *per_block)
+{
+    int64_t g = kPatchSlots / tiles_n;
+    g = g < 1 ? 1 : (g > tiles_m ? tiles_m : g);
+    *per_block = ceil_div(tiles_m, g);
+    *G = ceil_div(tiles_m, *per_block);          // the fewest blocks that still take per_block tiles each
+}
+
+// Does the patch path apply, and does it pay?  Measured against the gathering tile kernel on the
+// layers of the Sec. 6.3 network at batch 32 - 1024: 2 - 10 % faster from 512 tiles on for 128
+// channels and for 256 channels with tiles inside one image; with longer filters (more LDS to fill
+// per block, fewer tiles to spread it over) only once a block walks 8 row tiles.
+bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
+                    int stride, int pad, int H2, int W2)
+{
+    PatchGeom g;
+    size_t lds;
+    if (!aligned(in, 16) || !aligned(filt, 16) ||
+        !make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, &g, &lds))
+        return false;
+    const int64_t pix_img = (int64_t)H2 * W2;
+    const int64_t tiles_m = g.nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g.nimg);
+    const int64_t tiles_n = ceil_div(L2, kPBN);
+    if (tiles_m * tiles_n < kPatchSlots)
+        return false;
+    int64_t G, per_block;
+    patch_grid(tiles_m, tiles_n, &G, &per_block);
+    const int cpp = C / 128;
+    return cpp == 1 || (cpp == 2 && g.nimg == 1) || per_block >= 8;
+}
+
+int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                       const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2, int kh, int kw,
+                       int stride, int pad, int H2, int W2, int pool_log2w, hipStream_t stream)
+{
+    PatchGeom g;
+    size_t lds;
+    if (!make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, &g, &lds))
+        return ESP_ESHAPE;
+    const int64_t pix_img = (int64_t)H2 * W2;
+    const int64_t tiles_m = g.nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g.nimg);
+    const int64_t tiles_n = ceil_div(L2, kPBN);
+    if (tiles_m >= (1ll << 30) || tiles_n >= (1 << 20))
+        return ESP_ESHAPE;
+    int64_t G, per_block;
+    patch_grid(tiles_m, tiles_n, &G, &per_block);
+    const int K_true = kh * kw * C;
+    const StoreDots dots{C_out, (L2 % 4 == 0) && aligned(C_out, 16)};
+    const StoreSignBits bits{bits_out, thr, flip, (int)ceil_div(L2, 64), L2, pool_log2w};
+    const dim3 grid((unsigned)(G * tiles_n)), block(kPNT);
+    const uint32_t *f = reinterpret_cast<const uint32_t *>(filt);
+#define ESP_PATCH_LAUNCH(CPP, PCH, BITS)                                                                      \
+    hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS>), grid, block, lds, stream, g, f, dots, bits, L2,     \
+                       K_true, (int)tiles_m, (int)tiles_n, (int)G)
+    // patch chunks per thread: as many as the channel chunks of a pixel when that covers the patch
+    // (the Sec. 6.3 layers), else the maximum
+    const int cpp = C / 128;
+    const bool small_patch = g.patch_chunks <= cpp * kPNT;
+#define ESP_PATCH_CASE(CPP)                                     \
+    if (bits_out) {                                             \
+        if (small_patch)                                        \
+            ESP_PATCH_LAUNCH(CPP, CPP, true);                   \
+        else                                                    \
+            ESP_PATCH_LAUNCH(CPP, 4, true);                     \
+    } else {                                                    \
+        if (small_patch)                                        \
+            ESP_PATCH_LAUNCH(CPP, CPP, false);                  \
+        else                                                    \
+            ESP_PATCH_LAUNCH(CPP, 4, false);                    \
+    }
+    if (cpp == 1) {
+        ESP_PATCH_CASE(1)
+    } else if (cpp == 2) {
+        ESP_PATCH_CASE(2)
+    } else {
+        ESP_PATCH_CASE(4)
+    }
+#undef ESP_PATCH_CASE
+#undef ESP_PATCH_LAUNCH
+    return launch_status();
+}
+
+} // namespace esp

@@ -125,6 +125,14 @@ int bconv_implicit_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_o
                           const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
                           int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w, int engine,
                           hipStream_t stream);
+// The same for stride-1 convolutions whose block tiles are whole image rows: filters resident in
+// LDS, the input streamed as patches (bconv_patch.hip).  bconv_patch_ok says whether a shape
+// qualifies; XOR-popcount engine only.
+bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
+                    int stride, int pad, int H2, int W2);
+int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
+                       const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2, int kh, int kw,
+                       int stride, int pad, int H2, int W2, int pool_log2w, hipStream_t stream);
 int bconv_mfma_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
                       const uint64_t *flip, uint64_t *bits_out, int B, int H, int W, int C, int L2,
                       int kh, int kw, int stride, int pad, int H2, int W2, int pool_log2w,

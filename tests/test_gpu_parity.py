@@ -456,6 +456,46 @@ def test_bconv_bn_sign_pack_pool2(B, H, W, C, L2, kh, kw, stride, pad, engine):
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
+# Stride-1 layers with at least 512 tiles of 128 pixels x 64 filters take the kernel that keeps the
+# filters in LDS and streams the input as patches (whole image rows per tile).  Cases: tiles inside
+# one image and tiles of two whole images with an odd batch (a half-empty last tile); 128, 256 and
+# 512 channels; a partial last word of filters; output widths 8, 16, 32 and 128; 1x1, 3x3, 5x5 and
+# 1x3 filters; blocks that walk 1, 2, 3 and 8 row tiles.  int32, thresholded and pooled outputs.
+PATCH_CONV_CASES = [
+    # B, H, W, C, L2, kh, kw, pad
+    (40, 32, 32, 128, 256, 3, 3, 1),
+    (33, 32, 32, 128, 100, 3, 3, 1),
+    (129, 8, 8, 128, 512, 3, 3, 1),
+    (64, 16, 16, 256, 256, 3, 3, 1),
+    (128, 2, 128, 128, 128, 3, 3, 1),
+    (256, 16, 16, 128, 64, 1, 1, 0),
+    (64, 32, 32, 128, 64, 5, 5, 2),
+    (150, 14, 16, 128, 128, 1, 3, 1),
+    (2048, 16, 16, 512, 64, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,L2,kh,kw,pad", PATCH_CONV_CASES)
+def test_bconv_whole_row_tiles(B, H, W, C, L2, kh, kw, pad):
+    rng = np.random.default_rng(B + 10 * H + 100 * C + kh + 1000 * L2 + 17)
+    x = _pm1(rng, (B, H, W, C))
+    f = _pm1(rng, (L2, kh, kw, C))
+    bnp = synth.bn_params(rng, L2)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(kh * kw * C)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    thr_d, flip_d = torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV)
+    xp, fp = _packed_dev(x), _packed_dev(f)
+    pre = oracle.conv_pm1(x, f, 1, pad, -1)
+    assert np.array_equal(esp.bconv(xp, fp, C, 1, pad).cpu().numpy(), pre)
+    act = oracle.bn_sign(pre, bnp, synth.BN_EPS)
+    del pre
+    got = esp.bconv_bn_sign_pack(xp, fp, C, thr_d, flip_d, 1, pad)
+    assert np.array_equal(esp.packed_to_numpy(got), oracle.pack_bits(act))
+    if esp.bconv_pool2_fusable(H, W, C, kh, kw, 1, pad):
+        got = esp.bconv_bn_sign_pack_pool2(xp, fp, C, thr_d, flip_d, 1, pad)
+        assert np.array_equal(esp.packed_to_numpy(got), oracle.pack_bits(oracle.maxpool_pm1(act, 2, 2)))
+
+
 def test_bconv_pool2_rejects_shapes_it_cannot_fuse():
     assert not esp.bconv_pool2_fusable(32, 32, 64, 3, 3, 1, 1)     # lowered-matrix path
     assert not esp.bconv_pool2_fusable(7, 8, 128, 3, 3, 1, 1)      # odd output height
