@@ -30,8 +30,15 @@ void unroll_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
     const piece_t *src = reinterpret_cast<const piece_t *>(in);
     piece_t *dst = reinterpret_cast<piece_t *>(out);
 
+    // Consecutive block ids run on different XCDs, each with its own L2.  Every input pixel is
+    // read kh * kw times, by the pieces of neighbouring lowered rows: dealt out by block id those
+    // reads would come from all eight L2s and the input would be fetched from memory by each of
+    // them.  So the grid (a multiple of 8 blocks) is cut into eight contiguous ranges of pieces,
+    // one per XCD: an XCD then sweeps one eighth of the output pixels and fetches the input
+    // under them once.
+    const uint32_t block = xcd_contiguous_block();
     const uint32_t stride_all = gridDim.x * blockDim.x;
-    for (uint32_t o = blockIdx.x * blockDim.x + threadIdx.x; o < total_pieces; o += stride_all) {
+    for (uint32_t o = block * blockDim.x + threadIdx.x; o < total_pieces; o += stride_all) {
         const uint32_t row = fd_div(o, d_rowlen);
         const uint32_t j = o - row * d_rowlen.div;       // piece within the lowered row
         const uint32_t tap = fd_div(j, d_cwv);
@@ -68,6 +75,8 @@ void bmaxpool_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out
     piece_t *dst = reinterpret_cast<piece_t *>(out);
 
     const uint32_t stride_all = gridDim.x * blockDim.x;
+    // (one front of blocks sweeping memory in block-id order: eight per-XCD fronts measured 5 % slower
+    // on this kernel, which reads every input word once)
     for (uint32_t o = blockIdx.x * blockDim.x + threadIdx.x; o < total_pieces; o += stride_all) {
         const uint32_t pix = fd_div(o, d_cwv);
         const uint32_t w = o - pix * d_cwv.div;
@@ -124,7 +133,9 @@ static int unroll_launch(const uint64_t *in, uint64_t *out, int B, int H, int W,
     const FastDiv d_kw = make_fastdiv((uint32_t)kw);
     const FastDiv d_w2 = make_fastdiv((uint32_t)W2);
     const FastDiv d_h2 = make_fastdiv((uint32_t)H2);
-    const unsigned grid = grid_for(pieces, 256);
+    unsigned grid = grid_for(pieces, 256);
+    if (grid >= 64)
+        grid = (grid + 7) / 8 * 8;       // eight equal block ranges, one per XCD (see the kernel)
     const bool stream_out = total_words * 8 > kStreamBytes;
 #define ESP_UNROLL_LAUNCH(V, S)                                                                    \
     hipLaunchKernelGGL((unroll_kernel<V, S>), dim3(grid), dim3(256), 0, stream, in, out, pieces, H, \

@@ -76,6 +76,15 @@ __host__ __device__ __forceinline__ uint64_t valid_cols_mask(int w, int N)
     return left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
 }
 
+// Consecutive block ids run on different XCDs (eight, each with its own L2).  For a grid that is a
+// multiple of 8 blocks this gives block b the logical index that cuts the grid into eight
+// contiguous ranges, one per XCD, so that neighbouring pieces of work share an L2.
+__device__ __forceinline__ uint32_t xcd_contiguous_block()
+{
+    const uint32_t per_xcd = gridDim.x / 8;
+    return (gridDim.x % 8 == 0) ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+}
+
 // Number of blocks for a grid-stride kernel.  Measured on MI355X, streaming kernels reach
 // their best HBM bandwidth when the grid covers the whole array with one item per thread
 // (blocks are dispatched in order, so the blocks in flight sweep memory as one front);
