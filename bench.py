@@ -586,6 +586,35 @@ def _paper_configs(torch, esp, synth, dev, steps, warmup):
             "ms": round(ms, 5), "tbops": round(tb, 2), "frac_of_valu_peak": round(tb / VALU_PEAK_TBOPS, 4),
             "mfma_alternative_ms": round(ms_m, 5), "mfma_alternative_tbops": round(bop / (ms_m * 1e-3) / 1e12, 2)}
         del A, B, C
+    # What bounds the small squares: the time of a product with 2048 x 2048 outputs is a fixed part
+    # (launch, first loads, epilogue and the 16 MiB of results) plus a part proportional to K.  The
+    # two are separated by timing K = 2048, 4096 and 8192 and fitting a line; K = 64 and a
+    # near-empty kernel (one block, one round of the register probe) show the launch floor.
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.SEED0 + 5)
+    size = 2048
+    C = torch.empty((size, size), dtype=torch.int32, device=dev)
+    times = {}
+    for k in (64, 2048, 4096, 8192):
+        A = torch.randint(-2**62, 2**62, (size, k // 64), device=dev, generator=g, dtype=torch.int64)
+        B = torch.randint(-2**62, 2**62, (size, k // 64), device=dev, generator=g, dtype=torch.int64)
+        fn = lambda: esp.bgemm(A, B, k, out=C)
+        _settle(fn, torch, min_ms=20.0, cap_ms=80.0)
+        times[k] = _events_ms(fn, 500, 3, torch)[0] * 1e3
+    sink = torch.empty(256, dtype=torch.int32, device=dev)
+    fn = lambda: esp.xor_popcount_probe(sink, 1, 1)
+    _settle(fn, torch, min_ms=10.0, cap_ms=40.0)
+    empty_us = _events_ms(fn, 1000, 10, torch)[0] * 1e3
+    slope = (times[8192] - times[2048]) / 6.0                     # us per 1024 bits of K
+    fixed = times[2048] - 2.0 * slope
+    peak_slope = 2.0 * size * size * 1024 / (VALU_PEAK_TBOPS * 1e12) * 1e6
+    out["small_square_decomposition"] = {
+        "outputs": "2048 x 2048 int32", "us_by_k": {str(k): round(v, 2) for k, v in times.items()},
+        "near_empty_kernel_period_us": round(empty_us, 2),
+        "fixed_part_us": round(fixed, 2), "us_per_1024_bits_of_k": round(slope, 3),
+        "k_part_frac_of_valu_peak": round(peak_slope / slope, 4),
+        "note": "time(K) = fixed + K-proportional part, fitted on K = 2048 .. 8192; at K = 2048 the fixed part "
+                "(launch gap, first loads, epilogue, result write) is %.0f %% of the launch" % (100.0 * fixed / times[2048])}
     return out
 
 

@@ -311,7 +311,13 @@ static int launch_tile(const ASrc &asrc, const uint32_t *b, const TileOut &o, in
         if (big_tiles >= 512 || quantum > 64)
             return launch_tile2<128, 128, 8, 8, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     }
-    if (narrow_fills)
+    // 768 of the 128 x 64 tiles are resident at once (three per compute unit).  Between one and six
+    // such rounds the partly filled last round costs more than the smaller tile's extra LDS traffic:
+    // products of packed matrices then take 64 x 64 tiles (measured on squares: 12 % faster at 1.5
+    // rounds, 8 % at 2.04, 1 % at 2.7, 3 % at 4.2; 1 % slower from 6 rounds on and below one round).
+    const int64_t narrow_tiles = ceil_div(M, 128) * ceil_div(N, 64);
+    const bool few_rounds = !ASrc::kGathered && quantum == 1 && narrow_tiles > 768 && narrow_tiles < 6 * 768;
+    if (narrow_fills && !few_rounds)
         return launch_tile2<128, 64, 8, 4, ASrc, VEC16B>(asrc, b, o, M, N, K_true, row_dw, stream);
     // small products (dense layers at moderate batch, convolutions at batch 1): halve the
     // rows per lane so that twice as many waves share the work when the chip is not full
