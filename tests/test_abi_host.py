@@ -4,6 +4,7 @@ oracle's batch-norm + sign for every integer input (no GPU compute is called her
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -247,6 +248,71 @@ def test_bn_fold_f32_matches_oracle_around_every_threshold():
     want = oracle.sign(oracle.bn(x.astype(np.float64), g, b, m, v, synth.BN_EPS)) > 0
     got = (sgn[None, :] * x) >= thr[None, :]
     assert np.array_equal(got, want)
+
+
+_SANITIZER_MAIN = r"""
+// Drives the library's host code (status strings, both batch-norm folds) under AddressSanitizer and
+// UndefinedBehaviorSanitizer.  stdin: C, eps, then gamma / beta / mean / var (C floats each) as text;
+// stdout: thr flipbit (integer fold), then thr sgn as hex floats (float fold), one channel per line.
+#include <cstdio>
+#include <cstdint>
+#include <vector>
+#include "espresso_hip.h"
+int main()
+{
+    int C;
+    float eps;
+    if (std::scanf("%d %f", &C, &eps) != 2) return 2;
+    std::vector<float> p[4];
+    for (auto &v : p) { v.resize(C); for (int c = 0; c < C; ++c) if (std::scanf("%f", &v[c]) != 1) return 2; }
+    // exactly sized outputs: a write past either end is an error report
+    std::vector<int32_t> thr(C);
+    std::vector<uint64_t> flip((C + 63) / 64);
+    if (esp_bn_fold(p[0].data(), p[1].data(), p[2].data(), p[3].data(), eps, C, thr.data(), flip.data()) != ESP_OK) return 3;
+    std::vector<float> thrf(C), sgn(C);
+    if (esp_bn_fold_f32(p[0].data(), p[1].data(), p[2].data(), p[3].data(), eps, C, thrf.data(), sgn.data()) != ESP_OK) return 4;
+    for (int c = 0; c < C; ++c) std::printf("%d %d\n", thr[c], (int)((flip[c / 64] >> (c % 64)) & 1));
+    for (int c = 0; c < C; ++c) std::printf("%a %a\n", thrf[c], sgn[c]);
+    for (int st = -8; st <= 1; ++st) if (!esp_strerror(st)) return 5;
+    if (esp_bn_fold(nullptr, p[1].data(), p[2].data(), p[3].data(), eps, C, thr.data(), flip.data()) != ESP_EINVAL) return 6;
+    if (esp_bn_fold(p[0].data(), p[1].data(), p[2].data(), p[3].data(), eps, 0, thr.data(), flip.data()) == ESP_OK) return 7;
+    return 0;
+}
+"""
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """csrc/host.cpp built on the side with -fsanitize=address,undefined (CPU only; the GPU sources are not
+    part of it) and run on crafted + random channels, 70 of them so that the last flip word is partial: no
+    sanitizer report, and the folds it prints are the ones the product library computes."""
+    main = tmp_path / "san_main.cpp"
+    main.write_text(_SANITIZER_MAIN)
+    exe = tmp_path / "san_host"
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    subprocess.run(["g++", "-O1", "-g", "-std=c++17", "-ffp-contract=off", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan",
+                    "-I", os.path.join(root, "include"), str(main),
+                    os.path.join(root, "paper_1705_07175_amd", "csrc", "host.cpp"), "-o", str(exe)], check=True)
+    rng = np.random.default_rng(12)
+    C = 70
+    g, b, m, v = synth.bn_params(rng, C)
+    g[:8] = [0.0, 0.0, 1e-30, -1e-30, 1.0, -1.0, 2.0, -3.0]
+    b[:8] = [0.5, -0.5, 1.0, -1.0, 1e30, 1e30, -1e30, -1e30]
+    m[8:12] = [3e9, -3e9, 0.0, 1e-20]
+    text = "%d %r\n" % (C, float(synth.BN_EPS)) + "\n".join(" ".join(repr(float(x)) for x in a) for a in (g, b, m, v)) + "\n"
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(exe)], input=text, env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr[-2000:])
+    assert "runtime error" not in r.stderr and "Sanitizer" not in r.stderr, r.stderr[-2000:]
+    lines = r.stdout.split("\n")
+    thr, flip = esp.bn_fold(g, b, m, v, synth.BN_EPS)
+    for c in range(C):
+        t, f = lines[c].split()
+        assert int(t) == int(thr[c]) and int(f) == (int(flip[c // 64]) >> (c % 64)) & 1, c
+    thrf, sgn = esp.bn_fold_f32(g, b, m, v, synth.BN_EPS)
+    for c in range(C):
+        t, sg = lines[C + c].split()
+        assert float.fromhex(t) == float(thrf[c]) and float.fromhex(sg) == float(sgn[c]), c
 
 
 def test_bench_refuses_more_than_one_gpu():
