@@ -153,7 +153,7 @@ def main() -> int:
     ap.add_argument("--no-settle", action="store_true", help="with --only: skip the untimed clock-settle launches "
                     "(for counter-collecting profiler runs, which serialise every dispatch)")
     ap.add_argument("--only", default="", help="time ONE supporting workload and print its entry "
-                    "(for profiler runs): bgemm, bcnn<batch>, bmlp<batch>, " + ", ".join(SUPPORTING))
+                    "(for profiler runs): bgemm, small_squares, bcnn<batch>, bmlp<batch>, " + ", ".join(SUPPORTING))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -176,6 +176,9 @@ def main() -> int:
     if args.only.startswith(("bcnn", "bmlp")):
         kind, batch = args.only[:4], int(args.only[4:])
         print(json.dumps(_networks(torch, esp, nets, synth, dev, only=(kind, batch))))
+        return 0
+    if args.only == "small_squares":
+        print(json.dumps(_paper_configs(torch, esp, synth, dev, args.steps, args.warmup)))
         return 0
     if args.only and args.only != "bgemm":
         if args.only not in SUPPORTING:
@@ -604,6 +607,28 @@ def _paper_configs(torch, esp, synth, dev, steps, warmup):
     fn = lambda: esp.xor_popcount_probe(sink, 1, 1)
     _settle(fn, torch, min_ms=10.0, cap_ms=40.0)
     empty_us = _events_ms(fn, 1000, 10, torch)[0] * 1e3
+    # the same inside a HIP graph of 20 back-to-back launches (no host in the loop): the floor of a
+    # launch of 512 blocks that does nothing, and what the 16 MiB of int32 results cost on top of a
+    # product that writes packed sign bits instead (0.5 MiB)
+    def graph_us(fn, n=20):
+        fn()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(n):
+                fn()
+        _settle(gr.replay, torch, min_ms=10.0, cap_ms=40.0)
+        return _events_ms(gr.replay, 100, 3, torch)[0] / n * 1e3
+
+    sink512 = torch.empty(512 * 256, dtype=torch.int32, device=dev)
+    thr0 = torch.zeros(size, dtype=torch.int32, device=dev)
+    flip0 = torch.zeros(size // 64, dtype=esp.PACKED, device=dev)
+    bits0 = torch.empty((size, size // 64), dtype=esp.PACKED, device=dev)
+    in_graph = {"empty_kernel_512_blocks_us": round(graph_us(lambda: esp.xor_popcount_probe(sink512, 512, 1)), 2)}
+    for k in (64, 2048):
+        A = torch.randint(-2**62, 2**62, (size, k // 64), device=dev, generator=g, dtype=torch.int64)
+        B = torch.randint(-2**62, 2**62, (size, k // 64), device=dev, generator=g, dtype=torch.int64)
+        in_graph["k%d_int32_out_us" % k] = round(graph_us(lambda: esp.bgemm(A, B, k, out=C)), 2)
+        in_graph["k%d_sign_bits_out_us" % k] = round(graph_us(lambda: esp.bgemm_bn_sign_pack(A, B, k, thr0, flip0, out=bits0)), 2)
     slope = (times[8192] - times[2048]) / 6.0                     # us per 1024 bits of K
     fixed = times[2048] - 2.0 * slope
     peak_slope = 2.0 * size * size * 1024 / (VALU_PEAK_TBOPS * 1e12) * 1e6
@@ -612,6 +637,7 @@ def _paper_configs(torch, esp, synth, dev, steps, warmup):
         "near_empty_kernel_period_us": round(empty_us, 2),
         "fixed_part_us": round(fixed, 2), "us_per_1024_bits_of_k": round(slope, 3),
         "k_part_frac_of_valu_peak": round(peak_slope / slope, 4),
+        "inside_a_graph": in_graph,
         "note": "time(K) = fixed + K-proportional part, fitted on K = 2048 .. 8192; at K = 2048 the fixed part "
                 "(launch gap, first loads, epilogue, result write) is %.0f %% of the launch" % (100.0 * fixed / times[2048])}
     return out

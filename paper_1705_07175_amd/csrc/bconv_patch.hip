@@ -96,6 +96,30 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
     }
 
     // ---- patch fetch: chunk q of the patch <-> (image, patch row, patch pixel, part) -----
+    // What does not depend on the tile is worked out once per block when a thread has one or two
+    // chunks (the Sec. 6.3 layers): the chunk's offset from the tile's first input pixel, the
+    // range of tile rows for which its image row exists, its image within the tile.  Threads with
+    // four chunks decode on every fetch instead (the registers are needed elsewhere).
+    constexpr bool kKeepDecode = PCH <= 2;
+    uint32_t p_rel[kKeepDecode ? PCH : 1], p_ymin[kKeepDecode ? PCH : 1], p_il[kKeepDecode ? PCH : 1];
+    uint32_t p_dst[kKeepDecode ? PCH : 1];       // where the chunk goes in a patch buffer
+    if constexpr (kKeepDecode) {
+#pragma unroll
+        for (int i = 0; i < PCH; ++i) {
+            const uint32_t q = tid + i * kPNT;
+            const uint32_t qq = min(q, (uint32_t)g.patch_chunks - 1);
+            const uint32_t pix = qq / CPP, part = qq % CPP;
+            const uint32_t t = fd_div(pix, g.d_pcol), px = pix - t * g.pcol;
+            const uint32_t il = fd_div(t, g.d_prow), py = t - il * g.prow;
+            const int x = (int)px - g.pad;
+            const bool x_ok = q < (uint32_t)g.patch_chunks && (unsigned)x < (unsigned)g.W;
+            // offset of input pixel (il, py - pad, px - pad) from pixel (0, 0, 0), in dwords, modulo 2^32
+            p_rel[i] = ((il * g.H + py - g.pad) * g.W + x) * g.cdw + part * 4;
+            p_ymin[i] = (uint32_t)(g.pad - (int)py);     // the chunk's image row is y0 - p_ymin
+            p_il[i] = x_ok ? il : 0x7fffffffu;           // never below B - b0: such a chunk never counts
+            p_dst[i] = t * g.pitch + px * CPP + part;
+        }
+    }
     uint4 pp[PCH];                                // PCH * 256 chunks cover the patch
     uint32_t pkeep = 0;
     auto prefetch = [&](int tm) {
@@ -108,6 +132,18 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
             y0 = 0;
         }
         pkeep = 0;
+        if constexpr (kKeepDecode) {
+            const uint32_t tile_base = (b0 * g.H + y0) * g.W * g.cdw;
+            const uint32_t images_left = b0 < (uint32_t)g.B ? (uint32_t)g.B - b0 : 0u;
+#pragma unroll
+            for (int i = 0; i < PCH; ++i) {
+                const bool inside = p_il[i] < images_left && y0 - p_ymin[i] < (uint32_t)g.H;
+                const uint32_t off = inside ? tile_base + p_rel[i] : 0u;
+                pp[i] = *reinterpret_cast<const uint4 *>(g.in + off);
+                pkeep |= inside ? 1u << i : 0u;
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < PCH; ++i) {
             const uint32_t q = tid + i * kPNT;
@@ -130,9 +166,15 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
         for (int i = 0; i < PCH; ++i) {
             const uint32_t q = tid + i * kPNT;
             if (q < (uint32_t)g.patch_chunks) {
-                const uint32_t pix = q / CPP, part = q % CPP;
-                const uint32_t t = fd_div(pix, g.d_pcol), px = pix - t * g.pcol;   // t = image * prow + patch row
-                P[t * g.pitch + px * CPP + part] = keep4(pp[i], (pkeep >> i) & 1u);
+                uint32_t dst;
+                if constexpr (kKeepDecode) {
+                    dst = p_dst[i];
+                } else {
+                    const uint32_t pix = q / CPP, part = q % CPP;
+                    const uint32_t t = fd_div(pix, g.d_pcol), px = pix - t * g.pcol;   // t = image * prow + patch row
+                    dst = t * g.pitch + px * CPP + part;
+                }
+                P[dst] = keep4(pp[i], (pkeep >> i) & 1u);
             }
         }
     };
@@ -223,10 +265,10 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
             const uint4 *pa1 = pa + advance();
             const uint4 *pb1 = pb + kPatchBPitch;
             kgroup(std::true_type{}, pa, pa1, pb1, a0_even, b_even, a0_odd, b_odd);
-            const bool last = 2 >= g.KG;
+            const bool last = 2 >= g.KG;         // no k-group behind the pair: re-read the same chunks
             const int s2 = advance();
-            const uint4 *pa2 = last ? pa1 : pa1 + s2;
-            const uint4 *pb2 = last ? pb1 : pb1 + kPatchBPitch;
+            const uint4 *pa2 = pa1 + (last ? 0 : s2);
+            const uint4 *pb2 = pb1 + (last ? 0 : kPatchBPitch);
             kgroup(std::false_type{}, pa1, pa2, pb2, a0_odd, b_odd, a0_even, b_even);
             pa = pa2;
             pb = pb2;
@@ -239,10 +281,10 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
             const uint4 *pa1 = pa + advance();
             const uint4 *pb1 = pb + kPatchBPitch;
             kgroup(std::false_type{}, pa, pa1, pb1, a0_even, b_even, a0_odd, b_odd);
-            const bool last = k + 2 >= g.KG;     // no k-group behind the pair: re-read the same chunks
+            const bool last = k + 2 >= g.KG;
             const int s2 = advance();
-            const uint4 *pa2 = last ? pa1 : pa1 + s2;
-            const uint4 *pb2 = last ? pb1 : pb1 + kPatchBPitch;
+            const uint4 *pa2 = pa1 + (last ? 0 : s2);
+            const uint4 *pb2 = pb1 + (last ? 0 : kPatchBPitch);
             kgroup(std::false_type{}, pa1, pa2, pb2, a0_odd, b_odd, a0_even, b_even);
             pa = pa2;
             pb = pb2;
