@@ -405,9 +405,9 @@ static void patch_grid(int64_t tiles_m, int64_t tiles_n, int64_t *G, int64_t *pe
 }
 
 // Does the patch path apply, and does it pay?  Measured against the gathering tile kernel on the
-// layers of the Sec. 6.3 network at batch 32 - 1024: 2 - 10 % faster from 512 tiles on for 128
-// channels and for 256 channels with tiles inside one image; with longer filters (more LDS to fill
-// per block, fewer tiles to spread it over) only once a block walks 8 row tiles.
+// layers of the Sec. 6.3 network at batch 32 - 1024: 3 - 10 % faster from 512 tiles on for 128 and
+// 256 channels (even with two row tiles per block); with 512 channels (37 KB of filters to bring
+// into LDS per block) 3 % slower at two row tiles per block, level at four, 2 % faster at eight.
 bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
                     int stride, int pad, int H2, int W2)
 {
@@ -424,7 +424,7 @@ bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int 
     int64_t G, per_block;
     patch_grid(tiles_m, tiles_n, &G, &per_block);
     const int cpp = C / 128;
-    return cpp == 1 || (cpp == 2 && g.nimg == 1) || per_block >= 8;
+    return cpp <= 2 || per_block >= 8;
 }
 
 int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
