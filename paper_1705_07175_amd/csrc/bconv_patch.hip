@@ -29,7 +29,6 @@ constexpr int kPTM = 8, kPTN = 4;          // counters per lane
 constexpr int kPTX = kPBN / kPTN, kPTY = kPBM / kPTM, kPNT = kPTX * kPTY;   // 16 x 16 lanes
 constexpr int kPatchMaxChunksPerThread = 4;   // a patch is at most 4 * 256 chunks of 16 bytes
 constexpr int kPatchMaxKG = 36;            // k-groups (128 bits each) of a filter: 3 x 3 x 512 channels
-constexpr int kPatchBBatch = kPatchMaxKG / 4;   // filter chunks per thread, all in flight at once
 constexpr int kPatchBPitch = kPBN + 1;     // chunks per k-group of the filter slab (+1: bank skew)
 constexpr int kPatchSlots = 2 * 256;       // blocks of a launch: two per compute unit
 
@@ -77,9 +76,11 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
         return;
 
     // ---- the block's filters: all K of 64 rows, fetched once.  Four threads share a row and take
-    // every fourth k-group of it, all of its loads in flight at once; column nl is register column
+    // every fourth k-group of it; column nl is register column
     // nl % 4 of lane nl / 4 -------------------------------------------------------------------
     {
+        // chunks a thread has in flight: all of a 3 x 3 filter's at once (9 * CPP k-groups over 4 threads)
+        constexpr int kPatchBBatch = (9 * CPP + 3) / 4;
         const int nl = tid >> 2, kq = tid & 3;
         const uint32_t *brow = filt + (int64_t)min(n0 + nl, N - 1) * (g.KG * 4);
         uint4 *bdst = Bs + (nl % 4) * kPTX + nl / 4;
