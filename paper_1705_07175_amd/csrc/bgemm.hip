@@ -428,8 +428,15 @@ static int launch_few(const ASrc &asrc, const uint32_t *b, const TileOut &o, int
                       int64_t K_true, int64_t row_dw, hipStream_t stream)
 {
     const int64_t nch = row_dw / 4;
-    const int waves = (int)(nch < 16 ? nch : 16);        // the waves of a block split K
-    const dim3 grid((unsigned)ceil_div(M, 64), (unsigned)(ceil_div(N, 64) * 8)), block((unsigned)(waves * kWave));
+    const dim3 grid((unsigned)ceil_div(M, 64), (unsigned)(ceil_div(N, 64) * 8));
+    // The waves of a block split K: up to 16 while every CU gets at most one block.  A CU holds
+    // 28 waves of this kernel (its 103 scalar registers allow 7 per SIMD), i.e. one block of 16
+    // waves but three of 8: with more blocks than CUs, 8 waves keep all of them resident instead of
+    // running two rounds (256 x 1024 x 8192: 10.2 -> 8.7 us, 64 x 4096 x 4096: 7.9 -> 6.4 us; grids
+    // of at most 256 blocks lose 5-30 % with 8).
+    const int wmax = (int64_t)grid.x * grid.y > 256 ? 8 : 16;
+    const int waves = (int)(nch < wmax ? nch : wmax);
+    const dim3 block((unsigned)(waves * kWave));
     hipLaunchKernelGGL((bfew_bits_kernel<ASrc>), grid, block, 0, stream, asrc, b, o.thr, o.flip,
                        reinterpret_cast<uint8_t *>(o.bits), (int)M, (int)N, (int)K_true, (int)row_dw,
                        o.pool_log2w);
