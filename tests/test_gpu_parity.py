@@ -359,7 +359,9 @@ def test_bgemm_bn_sign_pack(M, N, K, engine):
 # 8 columns = one output byte per block): K from one 16-byte chunk to more chunks than waves,
 # M around the 64-row groups, N around the byte and word boundaries
 @pytest.mark.parametrize("M,N,K", [(9, 8, 128), (63, 9, 256), (64, 64, 4608), (65, 71, 2304), (200, 130, 1152),
-                                   (256, 256, 2304), (1000, 100, 384), (33, 500, 8192 + 128), (12, 1024, 8192)])
+                                   (256, 256, 2304), (1000, 100, 384), (33, 500, 8192 + 128), (12, 1024, 8192),
+                                   # more blocks than compute units: 8 waves per block instead of 16
+                                   (200, 1000, 8192 + 128), (64, 4096, 4096), (100, 2100, 640)])
 def test_bgemm_bn_sign_pack_few_rows(M, N, K):
     rng = np.random.default_rng(M * 3 + N * 5 + K)
     a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
