@@ -9,9 +9,15 @@
 // A lane owns 8 consecutive pixels of one image row, so its eight operands of a k-group are
 // one LDS address plus immediates, and that address advances by one 16-byte chunk per
 // k-group (by the row pitch when dy changes).  A 3 x 3 layer's K is short (1152 - 4608 bits):
-// the block's 64 filters stay in LDS for all of it, and the block walks several row tiles,
+// the block's 64 or 128 filters stay in LDS for all of it, and the block walks several row tiles,
 // fetching the next patch (1 - 4 chunks per thread) while it counts the current one, so that
 // after the first tile nothing waits for memory.  Per tile: one barrier.
+// With 128 filters per block a lane keeps 8 x 8 counters: every operand read from LDS then
+// serves twice as many xor + popcount pairs (12 reads per 128 pairs become 16 per 256), which
+// is what two waves per SIMD need to keep the vector ALUs fed (conv2 of the Sec. 6.3 network at
+// batch 256: 60.9 -> 57.4 us; conv4: 58.9 -> 56.5).  It is taken whenever the layer has a
+// multiple of 128 filters, their slab fits LDS beside the patches (up to 256 channels for a
+// 3 x 3 layer) and the grid still gets a tile per block.
 //
 // Used for stride-1 convolutions on 128, 256 or 512 channels whose output width is a power
 // of two between 8 and 128 (the layers of the Sec. 6.3 network); everything else takes the
@@ -24,12 +30,13 @@
 
 namespace esp {
 
-constexpr int kPBM = 128, kPBN = 64;       // block tile: output pixels x filters
-constexpr int kPTM = 8, kPTN = 4;          // counters per lane
-constexpr int kPTX = kPBN / kPTN, kPTY = kPBM / kPTM, kPNT = kPTX * kPTY;   // 16 x 16 lanes
+// Block tile: 128 output pixels x 64 or 128 filters; a lane keeps 8 x TN counters, TN = 4 or 8
+// (its columns are TN / 4 runs of four, 64 apart, as in the tile kernel).
+constexpr int kPBM = 128;
+constexpr int kPTM = 8;
+constexpr int kPTX = 16, kPTY = kPBM / kPTM, kPNT = kPTX * kPTY;   // 16 x 16 lanes
 constexpr int kPatchMaxChunksPerThread = 4;   // a patch is at most 4 * 256 chunks of 16 bytes
 constexpr int kPatchMaxKG = 36;            // k-groups (128 bits each) of a filter: 3 x 3 x 512 channels
-constexpr int kPatchBPitch = kPBN + 1;     // chunks per k-group of the filter slab (+1: bank skew)
 constexpr int kPatchSlots = 2 * 256;       // blocks of a launch: two per compute unit
 
 struct PatchGeom {
@@ -50,17 +57,19 @@ struct PatchGeom {
     FastDiv d_pcol, d_prow, d_tpi;         // divisions by pcol, prow, tiles per image
 };
 
-template <int CPP, int PCH, bool BITS>
-__global__ __launch_bounds__(kPNT, 3)
+template <int CPP, int PCH, bool BITS, int TN>
+__global__ __launch_bounds__(kPNT, TN == 4 ? 3 : 2)
 void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, const StoreDots dots,
                         const StoreSignBits bits, int N, int K_true, int tiles_m, int tiles_n, int G)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
+    constexpr int kPTN = TN, kPBN = kPTX * TN, kPWords = kPBN / 64;
+    constexpr int kPatchBPitch = kPBN + 1;     // chunks per k-group of the filter slab (+1: bank skew)
     uint4 *Bs = reinterpret_cast<uint4 *>(smem_raw);                     // [KG][kPatchBPitch]
     uint4 *P0 = Bs + g.KG * kPatchBPitch;                                // two patch buffers
     uint4 *P1 = P0 + g.patch_lds_chunks;
-    uint64_t *wt = reinterpret_cast<uint64_t *>(P1 + g.patch_lds_chunks);  // [kPBM] words for the pooled epilogue
-    uint64_t *flip_s = wt + kPBM;                                        // the block's flip word
+    uint64_t *wt = reinterpret_cast<uint64_t *>(P1 + g.patch_lds_chunks);  // [kPBM][kPWords] words for the pooled epilogue
+    uint64_t *flip_s = wt + kPBM * kPWords;                              // the block's flip words (two slots)
     int *lim_s = reinterpret_cast<int *>(flip_s + 2);                    // [kPBN] mismatch limits (16-byte aligned)
 
     const int tid = threadIdx.x;
@@ -76,14 +85,14 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
         return;
 
     // ---- the block's filters: all K of 64 rows, fetched once.  Four threads share a row and take
-    // every fourth k-group of it; column nl is register column
-    // nl % 4 of lane nl / 4 -------------------------------------------------------------------
-    {
+    // every fourth k-group of it; column nl is register column 4 (nl / 64) + nl % 4 of lane
+    // (nl % 64) / 4 ---------------------------------------------------------------------------
+    for (int nl0 = 0; nl0 < kPBN; nl0 += 64) {
         // chunks a thread has in flight: all of a 3 x 3 filter's at once (9 * CPP k-groups over 4 threads)
         constexpr int kPatchBBatch = (9 * CPP + 3) / 4;
-        const int nl = tid >> 2, kq = tid & 3;
+        const int nl = nl0 + (tid >> 2), kq = tid & 3;
         const uint32_t *brow = filt + (int64_t)min(n0 + nl, N - 1) * (g.KG * 4);
-        uint4 *bdst = Bs + (nl % 4) * kPTX + nl / 4;
+        uint4 *bdst = Bs + ((nl0 / 64) * 4 + nl % 4) * kPTX + (nl % 64) / 4;
         for (int kg = kq; kg < g.KG; kg += 4 * kPatchBBatch) {
             uint4 bv[kPatchBBatch];
 #pragma unroll
@@ -186,8 +195,10 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
     if constexpr (BITS) {
         if (tid < kPBN)
             lim_s[tid] = bits.mismatch_limit(n0 + tid, N, K_true);
-        if (tid == 0)
-            *flip_s = tn < bits.Nw ? bits.flip[tn] & valid_cols_mask(tn, N) : 0ull;
+        if (tid < kPWords) {
+            const int w = tn * kPWords + tid;
+            flip_s[tid] = w < bits.Nw ? bits.flip[w] & valid_cols_mask(w, N) : 0ull;
+        }
     }
     commit(P0);
     __syncthreads();
@@ -300,21 +311,29 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
         // ---- epilogue -----------------------------------------------------------------
         const int m0 = tm * kPBM;
         if constexpr (BITS) {
-            const int4 l4 = *reinterpret_cast<const int4 *>(&lim_s[tx * 4]);
-            const int lim[kPTN] = {l4.x, l4.y, l4.z, l4.w};
-            const uint64_t flipw = *flip_s;
-            LaneWord lw = bits.template tile_8x4<kPTY>(acc, lim, tx, ty);
-            lw.rl = r0 + (tx & 7);               // lane tx < 8 holds the word of the lane row's pixel tx
-            const uint64_t word = lw.have ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flipw) : 0ull;
+            int lim[kPTN];
+#pragma unroll
+            for (int jg = 0; jg < kPWords; ++jg) {
+                const int4 l4 = *reinterpret_cast<const int4 *>(&lim_s[jg * 64 + tx * 4]);
+                lim[jg * 4] = l4.x, lim[jg * 4 + 1] = l4.y, lim[jg * 4 + 2] = l4.z, lim[jg * 4 + 3] = l4.w;
+            }
+            LaneWord lw;
+            if constexpr (TN == 4)
+                lw = bits.template tile_8x4<kPTY>(acc, lim, tx, ty);
+            else
+                lw = bits.template tile<kPTY>(acc, lim, tx, ty);
+            lw.rl = r0 + (tx & 7);               // lane tx holds word tx / 8 of the lane row's pixel tx % 8
+            const uint64_t word = lw.have ? ((((uint64_t)lw.hi << 32) | lw.lo) ^ flip_s[lw.wl]) : 0ull;
+            const int w = tn * kPWords + lw.wl;
             if (bits.pool_log2w == 0) {
-                if (lw.have && m0 + lw.rl < g.M && tn < bits.Nw)
-                    bits.out[(int64_t)(m0 + lw.rl) * bits.Nw + tn] = word;
+                if (lw.have && m0 + lw.rl < g.M && w < bits.Nw)
+                    bits.out[(int64_t)(m0 + lw.rl) * bits.Nw + w] = word;
             } else {
                 // 2x2 max-pool of +-1 values = OR of the sign bits of the tile's row pairs
                 if (lw.have)
-                    wt[lw.rl] = word;
+                    wt[lw.rl * kPWords + lw.wl] = word;
                 __syncthreads();
-                pool_tile_store<kPBM, 1, kPNT>(wt, bits.out, m0, n0, g.M, bits.Nw, bits.pool_log2w, tid);
+                pool_tile_store<kPBM, kPWords, kPNT>(wt, bits.out, m0, n0, g.M, bits.Nw, bits.pool_log2w, tid);
             }
         } else {
 #pragma unroll
@@ -330,8 +349,9 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
 
 // Geometry of the patch path for a shape, or false if the shape does not qualify.
 static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int kh, int kw, int stride, int pad,
-                            int H2, int W2, PatchGeom *g, size_t *lds_bytes)
+                            int H2, int W2, int tn, PatchGeom *g, size_t *lds_bytes)
 {
+    const int pbn = kPTX * tn;                   // filters per block tile
     if (stride != 1 || C % 128 != 0)
         return false;
     const int cpp = C / 128;
@@ -362,7 +382,7 @@ static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int 
         return false;
     const int pitch = pcol * cpp + 1;
     const int64_t patch_lds = (int64_t)nimg * prow * pitch;
-    const size_t lds = (size_t)(KG * kPatchBPitch + 2 * patch_lds) * 16 + kPBM * 8 + 16 + kPBN * 4;
+    const size_t lds = (size_t)(KG * (pbn + 1) + 2 * patch_lds) * 16 + (size_t)kPBM * 8 * (pbn / 64) + 16 + pbn * 4;
     if (lds > 64 * 1024)
         return false;
     const int cdw = 2 * (C / 64);
@@ -405,27 +425,40 @@ static void patch_grid(int64_t tiles_m, int64_t tiles_n, int64_t *G, int64_t *pe
     *G = ceil_div(tiles_m, *per_block);          // the fewest blocks that still take per_block tiles each
 }
 
-// Does the patch path apply, and does it pay?  Measured against the gathering tile kernel on the
-// layers of the Sec. 6.3 network at batch 32 - 1024: 3 - 10 % faster from 512 tiles on for 128 and
-// 256 channels (even with two row tiles per block); with 512 channels (37 KB of filters to bring
-// into LDS per block) 3 % slower at two row tiles per block, level at four, 2 % faster at eight.
+// Counters per lane for a shape: 8 x 8 (128 filters per block: half the operand reads per pair)
+// when that still leaves every block of the grid a tile, else 8 x 4; 0 if the patch path does not
+// apply or does not pay.  Measured against the gathering tile kernel on the layers of the Sec. 6.3
+// network at batch 32 - 1024: 3 - 10 % faster from 512 tiles on for 128 and 256 channels (even with
+// two row tiles per block); with 512 channels (37 KB of filters to bring into LDS per block) 3 %
+// slower at two row tiles per block, level at four, 2 % faster at eight.
+static int patch_counters(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
+                          int stride, int pad, int H2, int W2, PatchGeom *g, size_t *lds)
+{
+    if (!aligned(in, 16) || !aligned(filt, 16))
+        return 0;
+    const int64_t pix_img = (int64_t)H2 * W2;
+    const int cpp = C / 128;
+    for (int tn = 8; tn >= 4; tn -= 4) {
+        if (!make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, tn, g, lds))
+            continue;
+        const int64_t tiles_m = g->nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g->nimg);
+        const int64_t tiles_n = ceil_div(L2, kPTX * tn);
+        if (tiles_m * tiles_n < kPatchSlots || (tn == 8 && L2 % 128 != 0))
+            continue;
+        int64_t G, per_block;
+        patch_grid(tiles_m, tiles_n, &G, &per_block);
+        if (cpp <= 2 || per_block >= 8)
+            return tn;
+    }
+    return 0;
+}
+
 bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
                     int stride, int pad, int H2, int W2)
 {
     PatchGeom g;
     size_t lds;
-    if (!aligned(in, 16) || !aligned(filt, 16) ||
-        !make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, &g, &lds))
-        return false;
-    const int64_t pix_img = (int64_t)H2 * W2;
-    const int64_t tiles_m = g.nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g.nimg);
-    const int64_t tiles_n = ceil_div(L2, kPBN);
-    if (tiles_m * tiles_n < kPatchSlots)
-        return false;
-    int64_t G, per_block;
-    patch_grid(tiles_m, tiles_n, &G, &per_block);
-    const int cpp = C / 128;
-    return cpp <= 2 || per_block >= 8;
+    return patch_counters(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds) != 0;
 }
 
 int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
@@ -434,11 +467,12 @@ int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out,
 {
     PatchGeom g;
     size_t lds;
-    if (!make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, &g, &lds))
+    const int tn = patch_counters(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds);
+    if (tn == 0)
         return ESP_ESHAPE;
     const int64_t pix_img = (int64_t)H2 * W2;
     const int64_t tiles_m = g.nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g.nimg);
-    const int64_t tiles_n = ceil_div(L2, kPBN);
+    const int64_t tiles_n = ceil_div(L2, kPTX * tn);
     if (tiles_m >= (1ll << 30) || tiles_n >= (1 << 20))
         return ESP_ESHAPE;
     int64_t G, per_block;
@@ -449,8 +483,14 @@ int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out,
     const dim3 grid((unsigned)(G * tiles_n)), block(kPNT);
     const uint32_t *f = reinterpret_cast<const uint32_t *>(filt);
 #define ESP_PATCH_LAUNCH(CPP, PCH, BITS)                                                                      \
-    hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS>), grid, block, lds, stream, g, f, dots, bits, L2,     \
-                       K_true, (int)tiles_m, (int)tiles_n, (int)G)
+    do {                                                                                                       \
+        if (tn == 8)                                                                                           \
+            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 8>), grid, block, lds, stream, g, f, dots,  \
+                               bits, L2, K_true, (int)tiles_m, (int)tiles_n, (int)G);                          \
+        else                                                                                                   \
+            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 4>), grid, block, lds, stream, g, f, dots,  \
+                               bits, L2, K_true, (int)tiles_m, (int)tiles_n, (int)G);                          \
+    } while (0)
     // patch chunks per thread: as many as the channel chunks of a pixel when that covers the patch
     // (the Sec. 6.3 layers), else the maximum
     const int cpp = C / 128;

@@ -474,6 +474,11 @@ PATCH_CONV_CASES = [
     (64, 32, 32, 128, 64, 5, 5, 2),
     (150, 14, 16, 128, 128, 1, 3, 1),
     (2048, 16, 16, 512, 64, 3, 3, 1),
+    # 128 filters per block (8 x 8 counters per lane): one, two and three filter tiles, a ragged
+    # last row tile of two-image tiles, 128 and 256 channels
+    (72, 32, 32, 128, 128, 3, 3, 1),
+    (261, 8, 8, 256, 512, 3, 3, 1),
+    (130, 16, 16, 128, 384, 3, 3, 1),
 ]
 
 
