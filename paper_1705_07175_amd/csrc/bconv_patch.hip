@@ -38,6 +38,7 @@ constexpr int kPTX = 16, kPTY = kPBM / kPTM, kPNT = kPTX * kPTY;   // 16 x 16 la
 constexpr int kPatchMaxChunksPerThread = 4;   // a patch is at most 4 * 256 chunks of 16 bytes
 constexpr int kPatchMaxKG = 36;            // k-groups (128 bits each) of a filter: 3 x 3 x 512 channels
 constexpr int kPatchSlots = 2 * 256;       // blocks of a launch: two per compute unit
+constexpr size_t kPatchMaxLdsWide = 144 * 1024;   // a block of two halves has the CU to itself
 
 struct PatchGeom {
     const uint32_t *in;      // packed NHWC input
@@ -57,53 +58,37 @@ struct PatchGeom {
     FastDiv d_pcol, d_prow, d_tpi;         // divisions by pcol, prow, tiles per image
 };
 
-template <int CPP, int PCH, bool BITS, int TN>
-__global__ __launch_bounds__(kPNT, TN == 4 ? 3 : 2)
+template <int CPP, int PCH, bool BITS, int TN, int NH>
+__global__ __launch_bounds__(kPNT * NH, NH == 2 ? 1 : (TN == 4 ? 3 : 2))
 void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, const StoreDots dots,
                         const StoreSignBits bits, int N, int K_true, int tiles_m, int tiles_n, int G)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     constexpr int kPTN = TN, kPBN = kPTX * TN, kPWords = kPBN / 64;
     constexpr int kPatchBPitch = kPBN + 1;     // chunks per k-group of the filter slab (+1: bank skew)
+    // NH = 2: the block is two halves of 256 threads that share the filter slab; each half walks
+    // its own row tiles (tile 2 p + half of the block's pair p) with its own patch buffers.
+    const int half = NH == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / kPNT);
     uint4 *Bs = reinterpret_cast<uint4 *>(smem_raw);                     // [KG][kPatchBPitch]
-    uint4 *P0 = Bs + g.KG * kPatchBPitch;                                // two patch buffers
+    uint4 *P0 = Bs + g.KG * kPatchBPitch + half * 2 * g.patch_lds_chunks;   // two patch buffers per half
     uint4 *P1 = P0 + g.patch_lds_chunks;
-    uint64_t *wt = reinterpret_cast<uint64_t *>(P1 + g.patch_lds_chunks);  // [kPBM][kPWords] words for the pooled epilogue
-    uint64_t *flip_s = wt + kPBM * kPWords;                              // the block's flip words (two slots)
+    uint64_t *wt_all = reinterpret_cast<uint64_t *>(Bs + g.KG * kPatchBPitch + NH * 2 * g.patch_lds_chunks);
+    uint64_t *wt = wt_all + half * kPBM * kPWords;                       // [kPBM][kPWords] words for the pooled epilogue
+    uint64_t *flip_s = wt_all + NH * kPBM * kPWords;                     // the block's flip words (two slots)
     int *lim_s = reinterpret_cast<int *>(flip_s + 2);                    // [kPBN] mismatch limits (16-byte aligned)
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x % kPNT;          // index inside the half
     const int tx = tid % kPTX;
     const int tyl = tid / kPTX;
     // the four lane rows of a wave take pixel groups 32 tile rows apart, so that their operand
     // reads fall into different LDS banks
     const int ty = (tyl % 4) * 4 + tyl / 4;
     const int tn = blockIdx.x % tiles_n;
-    const int first = blockIdx.x / tiles_n;      // this block walks row tiles first, first + G, ...
+    const int first = blockIdx.x / tiles_n;      // this block walks row tiles (pairs) first, first + G, ...
     const int n0 = tn * kPBN;
-    if (first >= tiles_m)
+    const int walks = (tiles_m + NH - 1) / NH;   // row tiles, or pairs of them
+    if (first >= walks)
         return;
-
-    // ---- the block's filters: all K of 64 rows, fetched once.  Four threads share a row and take
-    // every fourth k-group of it; column nl is register column 4 (nl / 64) + nl % 4 of lane
-    // (nl % 64) / 4 ---------------------------------------------------------------------------
-    for (int nl0 = 0; nl0 < kPBN; nl0 += 64) {
-        // chunks a thread has in flight: all of a 3 x 3 filter's at once (9 * CPP k-groups over 4 threads)
-        constexpr int kPatchBBatch = (9 * CPP + 3) / 4;
-        const int nl = nl0 + (tid >> 2), kq = tid & 3;
-        const uint32_t *brow = filt + (int64_t)min(n0 + nl, N - 1) * (g.KG * 4);
-        uint4 *bdst = Bs + ((nl0 / 64) * 4 + nl % 4) * kPTX + (nl % 64) / 4;
-        for (int kg = kq; kg < g.KG; kg += 4 * kPatchBBatch) {
-            uint4 bv[kPatchBBatch];
-#pragma unroll
-            for (int u = 0; u < kPatchBBatch; ++u)
-                bv[u] = *reinterpret_cast<const uint4 *>(brow + min(kg + 4 * u, g.KG - 1) * 4);
-#pragma unroll
-            for (int u = 0; u < kPatchBBatch; ++u)
-                if (kg + 4 * u < g.KG)
-                    bdst[(kg + 4 * u) * kPatchBPitch] = bv[u];
-        }
-    }
 
     // ---- patch fetch: chunk q of the patch <-> (image, patch row, patch pixel, part) -----
     // What does not depend on the tile is worked out once per block when a thread has one or two
@@ -188,7 +173,29 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
             }
         }
     };
-    prefetch(first);
+    prefetch(min(first * NH + half, tiles_m - 1));
+
+    // ---- the block's filters: all K of 64 rows per pass, fetched once (behind the first patch's
+    // loads, so that the two trips to memory overlap: a block with one or two tiles notices).  Four
+    // threads share a row and take every fourth k-group of it; column nl is register column 4 (nl / 64) + nl % 4 of lane
+    // (nl % 64) / 4 ---------------------------------------------------------------------------
+    for (int nl0 = 64 * half; nl0 < kPBN; nl0 += 64 * NH) {
+        // chunks a thread has in flight: all of a 3 x 3 filter's at once (9 * CPP k-groups over 4 threads)
+        constexpr int kPatchBBatch = (9 * CPP + 3) / 4;
+        const int nl = nl0 + (tid >> 2), kq = tid & 3;
+        const uint32_t *brow = filt + (int64_t)min(n0 + nl, N - 1) * (g.KG * 4);
+        uint4 *bdst = Bs + ((nl0 / 64) * 4 + nl % 4) * kPTX + (nl % 64) / 4;
+        for (int kg = kq; kg < g.KG; kg += 4 * kPatchBBatch) {
+            uint4 bv[kPatchBBatch];
+#pragma unroll
+            for (int u = 0; u < kPatchBBatch; ++u)
+                bv[u] = *reinterpret_cast<const uint4 *>(brow + min(kg + 4 * u, g.KG - 1) * 4);
+#pragma unroll
+            for (int u = 0; u < kPatchBBatch; ++u)
+                if (kg + 4 * u < g.KG)
+                    bdst[(kg + 4 * u) * kPatchBPitch] = bv[u];
+        }
+    }
 
     // thresholds and flip word of the block's 64 columns: the same for every tile, parked in LDS
     // (the main loop needs the registers)
@@ -211,14 +218,17 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
     const int wrap = g.pitch - g.kwc;            // extra chunks to the next patch row when dy advances
 
     int t = 0;
-    for (int tm = first; tm < tiles_m; tm += G, ++t) {
+    for (int walk = first; walk < walks; walk += G, ++t) {
+        // the half's row tile; an odd tile count leaves the last pair's second half a tile beyond
+        // the matrix: it counts the last tile's patch again and stores nothing (m0 >= M)
+        const int tm = walk * NH + half;
         const uint4 *P = (t & 1) ? P1 : P0;
         uint4 *Pn = (t & 1) ? P0 : P1;
         // The next patch is fetched and committed on every trip, also on the last one (where it is
         // the last tile again and never read): with both under a condition the compiler cannot
         // see that a fetch is always followed by its commit, and makes the next trip's fetch wait
         // for everything outstanding -- this trip's stores included.
-        prefetch(min(tm + G, tiles_m - 1));
+        prefetch(min((walk + G) * NH + half, tiles_m - 1));
 
         int acc[kPTM][kPTN];
 
@@ -349,7 +359,7 @@ void bconv_patch_kernel(const PatchGeom g, const uint32_t *__restrict__ filt, co
 
 // Geometry of the patch path for a shape, or false if the shape does not qualify.
 static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int kh, int kw, int stride, int pad,
-                            int H2, int W2, int tn, PatchGeom *g, size_t *lds_bytes)
+                            int H2, int W2, int tn, int nh, PatchGeom *g, size_t *lds_bytes)
 {
     const int pbn = kPTX * tn;                   // filters per block tile
     if (stride != 1 || C % 128 != 0)
@@ -382,8 +392,9 @@ static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int 
         return false;
     const int pitch = pcol * cpp + 1;
     const int64_t patch_lds = (int64_t)nimg * prow * pitch;
-    const size_t lds = (size_t)(KG * (pbn + 1) + 2 * patch_lds) * 16 + (size_t)kPBM * 8 * (pbn / 64) + 16 + pbn * 4;
-    if (lds > 64 * 1024)
+    const size_t lds = (size_t)(KG * (pbn + 1) + nh * 2 * patch_lds) * 16 + (size_t)nh * kPBM * 8 * (pbn / 64) + 16 + pbn * 4;
+    // two blocks of 256 threads per CU, or one of 512 (160 KB of LDS per CU)
+    if (lds > (nh == 2 ? kPatchMaxLdsWide : 64 * 1024))
         return false;
     const int cdw = 2 * (C / 64);
     if ((int64_t)B * H * W * cdw >= (1ll << 31) || (int64_t)B * pix_img >= (1ll << 31) || tiles_per_img >= (1ll << 30))
@@ -417,40 +428,51 @@ static bool make_patch_geom(const uint64_t *in, int B, int H, int W, int C, int 
 // Row tiles per block and blocks per filter tile for tiles_m x tiles_n tiles: the grid should be two
 // blocks per compute unit (two waves per SIMD keep the vector ALUs busy), each walking the same
 // number of row tiles.
-static void patch_grid(int64_t tiles_m, int64_t tiles_n, int64_t *G, int64_t *per_block)
+static void patch_grid(int64_t tiles_m, int64_t tiles_n, int64_t slots, int64_t *G, int64_t *per_block)
 {
-    int64_t g = kPatchSlots / tiles_n;
+    int64_t g = slots / tiles_n;
     g = g < 1 ? 1 : (g > tiles_m ? tiles_m : g);
     *per_block = ceil_div(tiles_m, g);
     *G = ceil_div(tiles_m, *per_block);          // the fewest blocks that still take per_block tiles each
 }
 
-// Counters per lane for a shape: 8 x 8 (128 filters per block: half the operand reads per pair)
-// when that still leaves every block of the grid a tile, else 8 x 4; 0 if the patch path does not
-// apply or does not pay.  Measured against the gathering tile kernel on the layers of the Sec. 6.3
-// network at batch 32 - 1024: 3 - 10 % faster from 512 tiles on for 128 and 256 channels (even with
-// two row tiles per block); with 512 channels (37 KB of filters to bring into LDS per block) 3 %
+// Block shape for a layer, or tn = 0 if the patch path does not apply or does not pay.
+//  * 8 x 8 counters per lane (128 filters per block: half the operand reads per pair) when the layer
+//    has a multiple of 128 filters, the slab fits and every block of the grid still gets a tile;
+//    with 512 channels the slab of 128 filters (74 KB) only fits when the block has the CU to
+//    itself: two halves of 256 threads then share it, each walking its own row tiles;
+//  * else 8 x 4 (64 filters per block).
+// Measured against the gathering tile kernel on the layers of the Sec. 6.3 network at batch
+// 32 - 1024: 3 - 10 % faster from 512 tiles on for 128 and 256 channels (even with two row tiles
+// per block); 8 x 4 counters on 512 channels (37 KB of filters to bring into LDS per block) 3 %
 // slower at two row tiles per block, level at four, 2 % faster at eight.
-static int patch_counters(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
-                          int stride, int pad, int H2, int W2, PatchGeom *g, size_t *lds)
+struct PatchShape { int tn, nh; };
+
+static PatchShape patch_shape(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh,
+                              int kw, int stride, int pad, int H2, int W2, PatchGeom *g, size_t *lds)
 {
     if (!aligned(in, 16) || !aligned(filt, 16))
-        return 0;
+        return PatchShape{0, 0};
     const int64_t pix_img = (int64_t)H2 * W2;
     const int cpp = C / 128;
-    for (int tn = 8; tn >= 4; tn -= 4) {
-        if (!make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, tn, g, lds))
+    static const PatchShape kTry[] = {{8, 1}, {8, 2}, {4, 1}};
+    for (const PatchShape &sh : kTry) {
+        if (sh.nh == 2 && cpp != 4)
+            continue;                            // (only instantiated for 512 channels)
+        if (!make_patch_geom(in, B, H, W, C, kh, kw, stride, pad, H2, W2, sh.tn, sh.nh, g, lds))
             continue;
         const int64_t tiles_m = g->nimg == 1 ? (int64_t)B * (pix_img / kPBM) : ceil_div(B, g->nimg);
-        const int64_t tiles_n = ceil_div(L2, kPTX * tn);
-        if (tiles_m * tiles_n < kPatchSlots || (tn == 8 && L2 % 128 != 0))
+        const int64_t walks = ceil_div(tiles_m, sh.nh);
+        const int64_t tiles_n = ceil_div(L2, kPTX * sh.tn);
+        const int64_t slots = kPatchSlots / sh.nh;
+        if (walks * tiles_n < slots || (sh.tn == 8 && L2 % 128 != 0))
             continue;
         int64_t G, per_block;
-        patch_grid(tiles_m, tiles_n, &G, &per_block);
-        if (cpp <= 2 || per_block >= 8)
-            return tn;
+        patch_grid(walks, tiles_n, slots, &G, &per_block);
+        if (cpp <= 2 || sh.nh == 2 || per_block >= 8)
+            return sh;
     }
-    return 0;
+    return PatchShape{0, 0};
 }
 
 bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int W, int C, int L2, int kh, int kw,
@@ -458,7 +480,7 @@ bool bconv_patch_ok(const uint64_t *in, const uint64_t *filt, int B, int H, int 
 {
     PatchGeom g;
     size_t lds;
-    return patch_counters(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds) != 0;
+    return patch_shape(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds).tn != 0;
 }
 
 int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out, const int32_t *thr,
@@ -467,7 +489,8 @@ int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out,
 {
     PatchGeom g;
     size_t lds;
-    const int tn = patch_counters(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds);
+    const PatchShape sh = patch_shape(in, filt, B, H, W, C, L2, kh, kw, stride, pad, H2, W2, &g, &lds);
+    const int tn = sh.tn;
     if (tn == 0)
         return ESP_ESHAPE;
     const int64_t pix_img = (int64_t)H2 * W2;
@@ -476,19 +499,41 @@ int bconv_patch_launch(const uint64_t *in, const uint64_t *filt, int32_t *C_out,
     if (tiles_m >= (1ll << 30) || tiles_n >= (1 << 20))
         return ESP_ESHAPE;
     int64_t G, per_block;
-    patch_grid(tiles_m, tiles_n, &G, &per_block);
+    patch_grid(ceil_div(tiles_m, sh.nh), tiles_n, kPatchSlots / sh.nh, &G, &per_block);
     const int K_true = kh * kw * C;
     const StoreDots dots{C_out, (L2 % 4 == 0) && aligned(C_out, 16)};
     const StoreSignBits bits{bits_out, thr, flip, (int)ceil_div(L2, 64), L2, pool_log2w};
-    const dim3 grid((unsigned)(G * tiles_n)), block(kPNT);
+    const dim3 grid((unsigned)(G * tiles_n)), block(kPNT * sh.nh);
     const uint32_t *f = reinterpret_cast<const uint32_t *>(filt);
+    if (sh.nh == 2) {
+        // 512 channels, 128 filters per block: one block of two halves per CU, more than the
+        // default 64 KB of dynamic LDS (the runtime wants that announced per kernel)
+        const int pch = g.patch_chunks <= 4 * kPNT ? 4 : 0;
+        if (pch != 4 || C != 512)
+            return ESP_ESHAPE;
+#define ESP_PATCH_WIDE(BITS)                                                                                    \
+        do {                                                                                                     \
+            auto kern = bconv_patch_kernel<4, 4, BITS, 8, 2>;                                                    \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    (int)lds) != hipSuccess)                                                     \
+                return ESP_ELAUNCH;                                                                              \
+            hipLaunchKernelGGL(kern, grid, block, lds, stream, g, f, dots, bits, L2, K_true, (int)tiles_m,       \
+                               (int)tiles_n, (int)G);                                                            \
+        } while (0)
+        if (bits_out)
+            ESP_PATCH_WIDE(true);
+        else
+            ESP_PATCH_WIDE(false);
+#undef ESP_PATCH_WIDE
+        return launch_status();
+    }
 #define ESP_PATCH_LAUNCH(CPP, PCH, BITS)                                                                      \
     do {                                                                                                       \
         if (tn == 8)                                                                                           \
-            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 8>), grid, block, lds, stream, g, f, dots,  \
+            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 8, 1>), grid, block, lds, stream, g, f, dots,  \
                                bits, L2, K_true, (int)tiles_m, (int)tiles_n, (int)G);                          \
         else                                                                                                   \
-            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 4>), grid, block, lds, stream, g, f, dots,  \
+            hipLaunchKernelGGL((bconv_patch_kernel<CPP, PCH, BITS, 4, 1>), grid, block, lds, stream, g, f, dots,  \
                                bits, L2, K_true, (int)tiles_m, (int)tiles_n, (int)G);                          \
     } while (0)
     // patch chunks per thread: as many as the channel chunks of a pixel when that covers the patch

@@ -479,6 +479,10 @@ PATCH_CONV_CASES = [
     (72, 32, 32, 128, 128, 3, 3, 1),
     (261, 8, 8, 256, 512, 3, 3, 1),
     (130, 16, 16, 128, 384, 3, 3, 1),
+    # 512 channels, 128 filters per block: blocks of two halves that walk pairs of row tiles; an odd
+    # number of row tiles (the last pair's second half has nothing to store), two-image tiles
+    (129, 8, 8, 512, 1024, 3, 3, 1),
+    (66, 16, 16, 512, 512, 3, 3, 1),
 ]
 
 
