@@ -383,7 +383,7 @@ def main() -> int:
 
 
 SUPPORTING = ("copy", "pack", "bn_sign_pack", "unroll", "bmaxpool", "bgemv", "bgemv_1g", "bconv_cfg2", "conv1_b256",
-              "bconv_conv2_b256", "bconv_conv4_b256", "bconv_conv6_b256",
+              "bconv_conv2_b256", "bconv_conv3_b256", "bconv_conv4_b256", "bconv_conv5_b256", "bconv_conv6_b256",
               "bconv_conv2_b256_mfma", "bconv_conv4_b256_mfma", "bconv_conv6_b256_mfma")
 
 
@@ -526,8 +526,9 @@ def _supporting_kernels(torch, esp, synth, dev, np, only="", steps=20, warmup=3,
                     "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s (bf16)",
                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                     "fp32_equivalent_tflops": round(tf / 3, 2)})
-    # the CNN's second and sixth layers at batch 256, fused threshold epilogue (bits out)
-    for name, h, c, l2 in (("bconv_conv2_b256", 32, 128, 128), ("bconv_conv4_b256", 16, 256, 256),
+    # the CNN's binary convolutions at batch 256, fused threshold epilogue (bits out)
+    for name, h, c, l2 in (("bconv_conv2_b256", 32, 128, 128), ("bconv_conv3_b256", 16, 128, 256),
+                           ("bconv_conv4_b256", 16, 256, 256), ("bconv_conv5_b256", 8, 256, 512),
                            ("bconv_conv6_b256", 8, 512, 512)):
         # the XOR-popcount engine is part of the default run; the matrix-core variant only on request
         if only not in ("", name, name + "_mfma"):
