@@ -507,6 +507,53 @@ def test_bconv_whole_row_tiles(B, H, W, C, L2, kh, kw, pad):
         assert np.array_equal(esp.packed_to_numpy(got), oracle.pack_bits(oracle.maxpool_pm1(act, 2, 2)))
 
 
+def _random_whole_row_shape(rng):
+    """A stride-1 layer that qualifies for the whole-row-tile kernels: 128 / 256 / 512 channels, output
+    width a power of two, output pixels per image a multiple or a divisor of 128, at least 512 tiles."""
+    while True:
+        C = int(rng.choice([128, 256, 512]))
+        W = int(rng.choice([8, 16, 32, 64]))
+        kh, kw = int(rng.choice([1, 3, 3, 3, 5])), int(rng.choice([1, 3, 3, 3, 5]))
+        pad = int(rng.choice([0, 1, 2]))
+        W2 = W + 2 * pad - kw + 1
+        if W2 < 8 or (W2 & (W2 - 1)):
+            continue
+        H2 = int(rng.choice([h for h in range(1, 65) if (h * W2) % 128 == 0 or 128 % (h * W2) == 0]))
+        H = H2 - 2 * pad + kh - 1
+        if H < 1:
+            continue
+        L2 = int(rng.choice([64, 100, 128, 200, 256, 384, 512]))
+        tiles_per_image = H2 * W2 / 128.0
+        B = int(np.ceil(512 / tiles_per_image / ((L2 + 63) // 64))) + int(rng.integers(0, 3))
+        if B * H2 * W2 * L2 * kh * kw * C <= 3e10 and B * H * W * C <= 2e8:
+            return B, H, W, C, L2, kh, kw, pad
+
+
+# seeded random shapes on top of the hand-picked ones above: filter heights and widths that differ,
+# no padding or more than the filter needs, tiles of several images, ragged last tiles, filter
+# counts that are no multiple of 64
+@pytest.mark.parametrize("seed", range(12))
+def test_bconv_whole_row_tiles_random_shapes(seed):
+    rng = np.random.default_rng(9000 + seed)
+    B, H, W, C, L2, kh, kw, pad = _random_whole_row_shape(rng)
+    x = _pm1(rng, (B, H, W, C))
+    f = _pm1(rng, (L2, kh, kw, C))
+    bnp = synth.bn_params(rng, L2)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(kh * kw * C)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    thr_d, flip_d = torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV)
+    xp, fp = _packed_dev(x), _packed_dev(f)
+    pre = oracle.conv_pm1(x, f, 1, pad, -1)
+    assert np.array_equal(esp.bconv(xp, fp, C, 1, pad).cpu().numpy(), pre), (B, H, W, C, L2, kh, kw, pad)
+    act = oracle.bn_sign(pre, bnp, synth.BN_EPS)
+    del pre
+    got = esp.bconv_bn_sign_pack(xp, fp, C, thr_d, flip_d, 1, pad)
+    assert np.array_equal(esp.packed_to_numpy(got), oracle.pack_bits(act)), (B, H, W, C, L2, kh, kw, pad)
+    if esp.bconv_pool2_fusable(H, W, C, kh, kw, 1, pad):
+        got = esp.bconv_bn_sign_pack_pool2(xp, fp, C, thr_d, flip_d, 1, pad)
+        assert np.array_equal(esp.packed_to_numpy(got), oracle.pack_bits(oracle.maxpool_pm1(act, 2, 2)))
+
+
 def test_bconv_pool2_rejects_shapes_it_cannot_fuse():
     assert not esp.bconv_pool2_fusable(32, 32, 64, 3, 3, 1, 1)     # lowered-matrix path
     assert not esp.bconv_pool2_fusable(7, 8, 128, 3, 3, 1, 1)      # odd output height
