@@ -374,6 +374,42 @@ def test_bgemm_bn_sign_pack_few_rows(M, N, K):
     assert np.array_equal(esp.packed_to_numpy(got), want)
 
 
+def _random_dense_shape(rng):
+    """(M, N, K) with every dimension drawn from one of three ranges: a handful, a few hundred, thousands."""
+    def pick(hi):
+        r = rng.random()
+        if r < 0.25:
+            return int(rng.integers(1, 17))
+        if r < 0.5:
+            return int(rng.integers(17, 300))
+        return int(rng.integers(300, hi))
+    while True:
+        M, N, K = pick(3000), pick(3000), pick(9000)
+        if M * N * K <= 2.5e10:
+            return M, N, K
+
+
+# seeded random shapes across the kernels' regimes (matrix-vector, few rows, small and large tiles,
+# ragged K and N), every engine: int32 dots and thresholded bits against the oracle
+@pytest.mark.parametrize("seed", range(16))
+def test_bgemm_random_shapes_all_engines(seed):
+    rng = np.random.default_rng(4100 + seed)
+    M, N, K = _random_dense_shape(rng)
+    a, b = _pm1(rng, (M, K)), _pm1(rng, (N, K))
+    want = oracle.dense_pm1(a, b)
+    ap, bp = _packed_dev(a), _packed_dev(b)
+    assert np.array_equal(esp.bgemm(ap, bp, K).cpu().numpy(), want), (M, N, K)
+    assert np.array_equal(esp.bgemm_mfma(ap, bp, K).cpu().numpy(), want), (M, N, K)
+    bnp = synth.bn_params(rng, N)
+    bnp = (bnp[0], bnp[1], (bnp[2] * np.sqrt(K)).astype(np.float32), bnp[3])
+    thr, flip = esp.bn_fold(*bnp, synth.BN_EPS)
+    thr_d, flip_d = torch.from_numpy(thr).to(DEV), esp.to_packed_tensor(flip, DEV)
+    want_bits = oracle.pack_bits(oracle.bn_sign(want, bnp, synth.BN_EPS))
+    for engine in (esp.ENGINE_XOR_POPCOUNT, esp.ENGINE_MFMA, esp.ENGINE_AUTO):
+        got = esp.bgemm_bn_sign_pack(ap, bp, K, thr_d, flip_d, engine=engine)
+        assert np.array_equal(esp.packed_to_numpy(got), want_bits), (M, N, K, engine)
+
+
 @pytest.mark.parametrize("engine,M,N,K", [(0, 2900, 2950, 640), (1, 2900, 2950, 640),
                                           (0, 2100, 1990, 640), (0, 32768 + 70, 100, 1152)])   # 128x64 tiles
 def test_bgemm_bn_sign_pack_large_tiles(engine, M, N, K):
